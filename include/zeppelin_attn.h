@@ -1,0 +1,133 @@
+/*
+ * zeppelin_attn.h -- C ABI of the single-GPU attention engine over packed variable-length sequences
+ * (the data-parallel hot path of Zeppelin, arXiv 2509.21841), hand-written HIP for gfx950 (MI355X).
+ *
+ * Common rules for every entry point
+ *  - Returns ZP_OK (0) or a negative error code; zp_strerror() gives the text. All argument checks
+ *    run on the host before anything is enqueued: on error nothing has been launched.
+ *  - "device" pointers are HIP device memory owned by the caller and must stay valid until the work
+ *    enqueued on `stream` has finished. "host" arrays are read before the call returns.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream). Calls only enqueue work:
+ *    no device synchronisation, no device memory allocation. The library keeps a small pool of pinned
+ *    host staging buffers (grown on demand) for its descriptor uploads.
+ *  - `ws` is caller-provided device scratch of at least zp_workspace_bytes(...) bytes, 256-byte aligned.
+ *    Its contents are undefined afterwards. Two calls that share one `ws` must be ordered on one stream.
+ *  - Layouts: token-major packed tensors. Q, O, dO, dQ are [T][Hq][d]; K, V, dK, dV are [T][Hkv][d],
+ *    bfloat16, head stride d, with an explicit token stride in ELEMENTS (so a fused QKV buffer works).
+ *    LSE is float32 [Hq][T], natural logarithm. Q head h reads KV head h / (Hq/Hkv).
+ *  - Sequence s owns tokens cu_seqlens[s] .. cu_seqlens[s+1]-1; cu_seqlens[0] = 0, non-decreasing,
+ *    cu_seqlens[S] = T. Zero-length sequences are legal. A token attends only to tokens of its own
+ *    sequence at the same or an earlier position (Sec. 2.1: lower-triangular mask; Sec. 2.3 / 3.2:
+ *    no cross-sequence attention, local sequences use a variable-length kernel).
+ *  - Supported: d in {64, 128}; Hq % Hkv == 0; bfloat16 inputs, float32 accumulation.
+ */
+#ifndef ZEPPELIN_ATTN_H
+#define ZEPPELIN_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ZP_OK 0
+#define ZP_EINVAL (-1)       /* null pointer, bad cu_seqlens, descriptor out of range, bad stride */
+#define ZP_EUNSUPPORTED (-2) /* head_dim not 64/128, Hq % Hkv != 0, row_bytes % 16 != 0 */
+#define ZP_EWORKSPACE (-3)   /* ws is NULL, misaligned or smaller than zp_workspace_bytes() */
+#define ZP_EHIP (-4)         /* a HIP runtime call failed; zp_strerror(ZP_EHIP) carries its text */
+
+#define ZP_MAX_PARTS 8
+
+/* Problem shape. T packed tokens, S sequences, Hq query heads, Hkv key/value heads, head dim d.
+ * scale multiplies q.k before the softmax; 0 selects 1/sqrt(d). */
+typedef struct {
+  int32_t T, S, Hq, Hkv, d;
+  float scale;
+} zp_shape;
+
+/* One (Q chunk, KV chunk) pair of one sequence (Sec. 3.2: a sequence on a ring of size G is cut into
+ * 2G equal-length chunks; each round a rank computes its Q chunks against the KV chunks in hand).
+ * q_tok0/k_tok0: first packed token of the Q / KV chunk; q_len/k_len: chunk lengths;
+ * q_pos0/k_pos0: position of the chunk's first token inside its sequence; key j of the chunk is visible
+ * to query i of the chunk iff k_pos0 + j <= q_pos0 + i; out_row0: the pair's first row in o_part/lse_part. */
+typedef struct {
+  int32_t q_tok0, q_len, k_tok0, k_len, q_pos0, k_pos0, out_row0;
+} zp_pair;
+
+/* One run of `len` output tokens starting at packed token out_tok0, each combined from n_parts partial
+ * rows: part p contributes rows part_row0[p] .. part_row0[p]+len-1 of o_part / lse_part. */
+typedef struct {
+  int32_t out_tok0, len, n_parts;
+  int32_t part_row0[ZP_MAX_PARTS];
+} zp_merge;
+
+/* Which entry point a workspace query is for. */
+enum { ZP_FN_FWD = 0, ZP_FN_BWD = 1, ZP_FN_PARTIAL = 2, ZP_FN_MERGE = 3 };
+
+/* Bytes of `ws` an entry point needs. n_desc: number of pairs (ZP_FN_PARTIAL) or merges (ZP_FN_MERGE),
+ * ignored otherwise. cu_seqlens_host may be NULL for ZP_FN_PARTIAL / ZP_FN_MERGE. Returns 0 on bad input. */
+size_t zp_workspace_bytes(int which_fn, const zp_shape *sh, const int32_t *cu_seqlens_host, int64_t n_desc);
+
+/* Causal softmax attention of every sequence of the packed batch (Sec. 3.2, local sequences; Sec. 2.1):
+ *   O[i,h,:] = sum_{j<=i} softmax_j(scale q_i.k_j) v_j ,   LSE[h,i] = log sum_{j<=i} exp(scale q_i.k_j).
+ * The host builds a work list of (sequence, query block) tiles ordered by descending number of visible
+ * key tiles -- the quadratic cost model |s|^2 of Alg. 2 applied per tile -- so that the heaviest tiles
+ * start first and the light tail fills the gaps.
+ * q,k,v: device bf16; o: device bf16 out; lse: device float32 [Hq][T] out; cu_seqlens_host: host [S+1]. */
+int varlen_attn_fwd(const void *q, const void *k, const void *v, int64_t q_stride, int64_t k_stride, int64_t v_stride,
+                    const int32_t *cu_seqlens_host, void *o, int64_t o_stride, float *lse, const zp_shape *sh, void *ws,
+                    size_t ws_bytes, void *stream);
+
+/* Backward of varlen_attn_fwd (Sec. 5.4: the backward mirrors the forward with about twice the work).
+ * Reads dO, Q, K, V and the forward's O and LSE; writes dQ [T][Hq][d], dK, dV [T][Hkv][d] (bf16). With
+ * P_ij = exp(scale q_i.k_j - LSE_i), D_i = dO_i.O_i, dS_ij = P_ij (dO_i.v_j - D_i):
+ *   dQ_i = scale sum_{j<=i} dS_ij k_j ;  dK_j = scale sum_{h in group} sum_{i>=j} dS_ij q_i ;
+ *   dV_j = sum_{h in group} sum_{i>=j} P_ij dO_i.
+ * Deterministic (no atomics): one kernel owns key/value rows, one owns query rows.
+ * dq/dk/dv token strides are dq_stride (= for dQ) and dkv_stride (for dK and dV). */
+int varlen_attn_bwd(const void *dout, const void *q, const void *k, const void *v, const void *o, const float *lse,
+                    int64_t do_stride, int64_t q_stride, int64_t k_stride, int64_t v_stride, int64_t o_stride,
+                    const int32_t *cu_seqlens_host, void *dq, void *dk, void *dv, int64_t dq_stride,
+                    int64_t dkv_stride, const zp_shape *sh, void *ws, size_t ws_bytes, void *stream);
+
+/* Partial attention of (Q chunk, KV chunk) pairs (Sec. 3.2, the per-round compute of ring attention):
+ * for each pair and head, softmax over only that KV chunk's causally visible keys, normalised by its
+ * own sum, with its own LSE. Rows with no visible key get LSE = -inf and O = 0.
+ * o_part: device float32 [part_rows][Hq][d]; lse_part: device float32 [Hq][part_rows]; every pair's row
+ * range must lie inside part_rows; ranges of different pairs must not overlap (not checked).
+ * sh->S is ignored, sh->T bounds the token offsets. pairs_host: host array of n_pairs. */
+int chunk_attn_partial(const void *q, const void *k, const void *v, int64_t q_stride, int64_t k_stride,
+                       int64_t v_stride, const zp_pair *pairs_host, int32_t n_pairs, float *o_part, float *lse_part,
+                       int64_t part_rows, const zp_shape *sh, void *ws, size_t ws_bytes, void *stream);
+
+/* Online-softmax combination of partial results (Sec. 3.2, "standard ring attention pattern"):
+ *   LSE = log sum_p exp(LSE_p),  O = sum_p exp(LSE_p - LSE) O_p ; parts with LSE_p = -inf weigh 0 and a
+ * row whose parts are all -inf gets LSE = -inf, O = 0. Writes O (bf16, token stride o_stride) and
+ * LSE [Hq][T] only for the tokens the merges cover. merges_host: host array of n_merges. */
+int lse_merge(const float *o_part, const float *lse_part, int64_t part_rows, const zp_merge *merges_host,
+              int32_t n_merges, void *o, int64_t o_stride, float *lse, const zp_shape *sh, void *ws, size_t ws_bytes,
+              void *stream);
+
+/* Token move of the remapping layer (Sec. 3.4: attention layout <-> token-balanced layout, and back).
+ * mode 0 (gather):  dst row i = src row idx[i];  mode 1 (scatter): dst row idx[i] = src row i.
+ * Rows are raw bytes: row_bytes % 16 == 0, src/dst 16-byte aligned and not overlapping. idx_dev: device
+ * int32 [n_rows], every entry in [0, n_rows) (a permutation for mode 1; not checked on the device). */
+int remap_tokens(const void *src, void *dst, int64_t row_bytes, const int32_t *idx_dev, int64_t n_rows, int32_t mode,
+                 void *stream);
+
+/* Host-only helper (no device work): descriptors of one sequence cut into C equal-length chunks
+ * (chunk c = positions [floor(cL/C), floor((c+1)L/C)) ). rank < 0: every causal pair (kc <= qc).
+ * rank in [0, C/2): only the pairs ring rank `rank` computes, i.e. Q chunks {rank, C-1-rank} (C even).
+ * tok0: first packed token of the sequence; row0: first free row of o_part. Fills pairs[] (capacity
+ * max_pairs) and merges[] (capacity max_merges, one per Q chunk); returns the number of pairs, sets
+ * *n_merges and *rows_used (partial rows consumed). Negative on error. */
+int zp_chunk_pairs(int32_t tok0, int32_t L, int32_t C, int32_t rank, int32_t row0, zp_pair *pairs, int32_t max_pairs,
+                   zp_merge *merges, int32_t max_merges, int32_t *n_merges, int64_t *rows_used);
+
+const char *zp_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,240 @@
+"""ctypes binding of libzeppelin_attn.so: argument marshalling only.
+
+Same names as the C ABI (include/zeppelin_attn.h). Tensors are torch CUDA(HIP) tensors used purely as device
+buffers; every step of the path runs in the library's HIP kernels. There is no CPU fallback: a missing
+library or a failing call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libzeppelin_attn.so")
+MAX_PARTS = 8
+FN_FWD, FN_BWD, FN_PARTIAL, FN_MERGE = 0, 1, 2, 3
+
+
+class ZpShape(ctypes.Structure):
+    _fields_ = [("T", ctypes.c_int32), ("S", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
+                ("d", ctypes.c_int32), ("scale", ctypes.c_float)]
+
+
+class ZpPair(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("q_tok0", "q_len", "k_tok0", "k_len", "q_pos0", "k_pos0", "out_row0")]
+
+
+class ZpMerge(ctypes.Structure):
+    _fields_ = [("out_tok0", ctypes.c_int32), ("len", ctypes.c_int32), ("n_parts", ctypes.c_int32),
+                ("part_row0", ctypes.c_int32 * MAX_PARTS)]
+
+
+class ZpError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"zeppelin_attn error {code}: {text}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Loads the built library; builds it first only if no built library exists."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from . import build as _build
+        _build.build()
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
+    L.zp_strerror.restype = ctypes.c_char_p
+    L.zp_strerror.argtypes = [ctypes.c_int]
+    L.zp_workspace_bytes.restype = sz
+    L.zp_workspace_bytes.argtypes = [ctypes.c_int, ctypes.POINTER(ZpShape), vp, i64]
+    L.varlen_attn_fwd.restype = ctypes.c_int
+    L.varlen_attn_fwd.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp, i64, vp, ctypes.POINTER(ZpShape), vp, sz, vp]
+    L.varlen_attn_bwd.restype = ctypes.c_int
+    L.varlen_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, vp, vp, vp, vp, i64, i64,
+                                  ctypes.POINTER(ZpShape), vp, sz, vp]
+    L.chunk_attn_partial.restype = ctypes.c_int
+    L.chunk_attn_partial.argtypes = [vp, vp, vp, i64, i64, i64, ctypes.POINTER(ZpPair), i32, vp, vp, i64,
+                                     ctypes.POINTER(ZpShape), vp, sz, vp]
+    L.lse_merge.restype = ctypes.c_int
+    L.lse_merge.argtypes = [vp, vp, i64, ctypes.POINTER(ZpMerge), i32, vp, i64, vp, ctypes.POINTER(ZpShape), vp, sz, vp]
+    L.remap_tokens.restype = ctypes.c_int
+    L.remap_tokens.argtypes = [vp, vp, i64, vp, i64, i32, vp]
+    L.zp_chunk_pairs.restype = ctypes.c_int
+    L.zp_chunk_pairs.argtypes = [i32, i32, i32, i32, i32, ctypes.POINTER(ZpPair), i32, ctypes.POINTER(ZpMerge), i32,
+                                 ctypes.POINTER(i32), ctypes.POINTER(i64)]
+    _lib = L
+    return L
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise ZpError(rc, lib().zp_strerror(rc).decode())
+
+
+def _stream_ptr(stream=None):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _cu_host(cu_seqlens) -> np.ndarray:
+    if isinstance(cu_seqlens, torch.Tensor):
+        cu_seqlens = cu_seqlens.cpu().numpy()
+    return np.ascontiguousarray(cu_seqlens, dtype=np.int32)
+
+
+def _tok_stride(t: torch.Tensor) -> int:
+    assert t.dim() == 3 and t.stride(2) == 1 and t.stride(1) == t.shape[2], "need [T,H,d] with contiguous heads"
+    return t.stride(0) if t.shape[0] > 1 else t.shape[1] * t.shape[2]
+
+
+_ws_cache: dict = {}
+
+
+def workspace(nbytes: int, device, tag: str = "default") -> torch.Tensor:
+    """A cached device scratch tensor of at least nbytes (256-byte aligned by the torch allocator)."""
+    key = (str(device), tag)
+    t = _ws_cache.get(key)
+    if t is None or t.numel() < nbytes:
+        t = torch.empty(max(int(nbytes), 4096), dtype=torch.uint8, device=device)
+        _ws_cache[key] = t
+    return t
+
+
+def workspace_bytes(which: int, shape: ZpShape, cu_host=None, n_desc: int = 0) -> int:
+    cup = cu_host.ctypes.data_as(ctypes.c_void_p) if cu_host is not None else None
+    return int(lib().zp_workspace_bytes(which, ctypes.byref(shape), cup, n_desc))
+
+
+def make_shape(T, S, Hq, Hkv, d, scale=0.0) -> ZpShape:
+    return ZpShape(int(T), int(S), int(Hq), int(Hkv), int(d), float(scale or 0.0))
+
+
+def varlen_attn_fwd(q, k, v, cu_seqlens, o=None, lse=None, scale=0.0, ws=None, stream=None):
+    """q [T,Hq,d], k/v [T,Hkv,d] bf16 device tensors -> (o [T,Hq,d] bf16, lse [Hq,T] f32)."""
+    cu = _cu_host(cu_seqlens)
+    T, Hq, d = q.shape
+    Hkv = k.shape[1]
+    sh = make_shape(T, len(cu) - 1, Hq, Hkv, d, scale)
+    if o is None:
+        o = torch.empty_like(q)
+    if lse is None:
+        lse = torch.empty((Hq, T), dtype=torch.float32, device=q.device)
+    need = workspace_bytes(FN_FWD, sh, cu)
+    if ws is None:
+        ws = workspace(need, q.device, "fwd")
+    _check(lib().varlen_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), _tok_stride(q), _tok_stride(k), _tok_stride(v),
+                                 cu.ctypes.data_as(ctypes.c_void_p), o.data_ptr(), _tok_stride(o), lse.data_ptr(),
+                                 ctypes.byref(sh), ws.data_ptr(), ws.numel(), _stream_ptr(stream)))
+    return o, lse
+
+
+def varlen_attn_bwd(dout, q, k, v, o, lse, cu_seqlens, dq=None, dk=None, dv=None, scale=0.0, ws=None, stream=None):
+    """-> (dq [T,Hq,d], dk [T,Hkv,d], dv [T,Hkv,d]) bf16."""
+    cu = _cu_host(cu_seqlens)
+    T, Hq, d = q.shape
+    Hkv = k.shape[1]
+    sh = make_shape(T, len(cu) - 1, Hq, Hkv, d, scale)
+    dq = torch.empty_like(q) if dq is None else dq
+    dk = torch.empty_like(k) if dk is None else dk
+    dv = torch.empty_like(v) if dv is None else dv
+    need = workspace_bytes(FN_BWD, sh, cu)
+    if ws is None:
+        ws = workspace(need, q.device, "bwd")
+    assert _tok_stride(dk) == _tok_stride(dv)
+    _check(lib().varlen_attn_bwd(dout.data_ptr(), q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
+                                 _tok_stride(dout), _tok_stride(q), _tok_stride(k), _tok_stride(v), _tok_stride(o),
+                                 cu.ctypes.data_as(ctypes.c_void_p), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(),
+                                 _tok_stride(dq), _tok_stride(dk), ctypes.byref(sh), ws.data_ptr(), ws.numel(),
+                                 _stream_ptr(stream)))
+    return dq, dk, dv
+
+
+def _pairs_array(pairs):
+    if isinstance(pairs, ctypes.Array):
+        return pairs, len(pairs)
+    arr = (ZpPair * max(len(pairs), 1))()
+    for n, p in enumerate(pairs):
+        vals = [p[f] for f, _ in ZpPair._fields_] if isinstance(p, dict) else list(p)
+        for (f, _), val in zip(ZpPair._fields_, vals):
+            setattr(arr[n], f, int(val))
+    return arr, len(pairs)
+
+
+def _merges_array(merges):
+    if isinstance(merges, ctypes.Array):
+        return merges, len(merges)
+    arr = (ZpMerge * max(len(merges), 1))()
+    for n, (tok0, ln, rows) in enumerate(merges):
+        arr[n].out_tok0, arr[n].len, arr[n].n_parts = int(tok0), int(ln), len(rows)
+        for p, r in enumerate(rows[:MAX_PARTS]):
+            arr[n].part_row0[p] = int(r)
+        if len(rows) > MAX_PARTS:
+            arr[n].n_parts = len(rows)  # rejected by the library
+    return arr, len(merges)
+
+
+def chunk_attn_partial(q, k, v, pairs, part_rows, o_part=None, lse_part=None, scale=0.0, ws=None, stream=None):
+    """-> (o_part [part_rows,Hq,d] f32, lse_part [Hq,part_rows] f32)."""
+    T, Hq, d = q.shape
+    Hkv = k.shape[1]
+    sh = make_shape(T, 0, Hq, Hkv, d, scale)
+    arr, n = _pairs_array(pairs)
+    if o_part is None:
+        o_part = torch.empty((part_rows, Hq, d), dtype=torch.float32, device=q.device)
+    if lse_part is None:
+        lse_part = torch.empty((Hq, part_rows), dtype=torch.float32, device=q.device)
+    need = workspace_bytes(FN_PARTIAL, sh, None, n)
+    if ws is None:
+        ws = workspace(need, q.device, "partial")
+    _check(lib().chunk_attn_partial(q.data_ptr(), k.data_ptr(), v.data_ptr(), _tok_stride(q), _tok_stride(k), _tok_stride(v),
+                                    arr, n, o_part.data_ptr(), lse_part.data_ptr(), int(part_rows), ctypes.byref(sh),
+                                    ws.data_ptr(), ws.numel(), _stream_ptr(stream)))
+    return o_part, lse_part
+
+
+def lse_merge(o_part, lse_part, merges, o, lse, ws=None, stream=None):
+    """Combines partial rows into o [T,Hq,d] bf16 and lse [Hq,T] f32 (only the tokens the merges cover)."""
+    part_rows, Hq, d = o_part.shape
+    T = o.shape[0]
+    sh = make_shape(T, 0, Hq, Hq, d, 0.0)
+    arr, n = _merges_array(merges)
+    need = workspace_bytes(FN_MERGE, sh, None, n)
+    if ws is None:
+        ws = workspace(need, o.device, "merge")
+    _check(lib().lse_merge(o_part.data_ptr(), lse_part.data_ptr(), int(part_rows), arr, n, o.data_ptr(), _tok_stride(o),
+                           lse.data_ptr(), ctypes.byref(sh), ws.data_ptr(), ws.numel(), _stream_ptr(stream)))
+    return o, lse
+
+
+def remap_tokens(src, idx, mode: int = 0, dst=None, stream=None):
+    """Row gather (mode 0: dst[i] = src[idx[i]]) or scatter (mode 1: dst[idx[i]] = src[i]); idx int32 on device."""
+    assert src.is_contiguous()
+    n = src.shape[0]
+    row_bytes = int(np.prod(src.shape[1:])) * src.element_size()
+    if dst is None:
+        dst = torch.empty_like(src)
+    _check(lib().remap_tokens(src.data_ptr(), dst.data_ptr(), int(row_bytes), idx.data_ptr(), int(n), int(mode),
+                              _stream_ptr(stream)))
+    return dst
+
+
+def chunk_pairs(tok0: int, L: int, C: int, rank: int = -1, row0: int = 0):
+    """Host helper: (pairs, merges, rows_used) as ctypes arrays for one sequence cut into C chunks."""
+    max_pairs = C * (C + 1) // 2
+    pairs = (ZpPair * max_pairs)()
+    merges = (ZpMerge * C)()
+    nm = ctypes.c_int32(0)
+    rows = ctypes.c_int64(0)
+    n = lib().zp_chunk_pairs(int(tok0), int(L), int(C), int(rank), int(row0), pairs, max_pairs, merges, C,
+                             ctypes.byref(nm), ctypes.byref(rows))
+    if n < 0:
+        _check(n)
+    return (ZpPair * n)(*pairs[:n]), (ZpMerge * nm.value)(*merges[:nm.value]), int(rows.value)

@@ -1,0 +1,77 @@
+// Online-softmax combination of partial attention results (Sec. 3.2, ring attention rounds):
+//   LSE = log sum_p exp(LSE_p),  O = sum_p exp(LSE_p - LSE) O_p.
+// Elementwise and HBM-bound: each lane owns 4 consecutive head-dim elements of one (row, head), reads the
+// n_parts partial LSEs (broadcast within the row) and n_parts float4, writes 4 bf16.
+#include "zp_common.h"
+
+#define ZP_MAX_PARTS 8
+struct zp_merge_dev {
+  int32_t out_tok0, len, n_parts;
+  int32_t part_row0[ZP_MAX_PARTS];
+};
+struct zp_merge_item { int32_t merge, row0; };  // a band of up to MERGE_ROWS rows of one merge
+
+namespace {
+constexpr int MERGE_NT = 256;
+constexpr int MERGE_ROWS = 8;
+
+__global__ __launch_bounds__(MERGE_NT) void lse_merge_kernel(const float *__restrict__ o_part, const float *__restrict__ lse_part,
+                                                             int64_t part_rows, const zp_merge_dev *__restrict__ merges,
+                                                             const zp_merge_item *__restrict__ items, int Hq, int d,
+                                                             __bf16 *__restrict__ o, int64_t o_stride, float *__restrict__ lse,
+                                                             int64_t T) {
+  const zp_merge_item it = items[blockIdx.x];
+  const zp_merge_dev mg = merges[it.merge];
+  int rows = mg.len - it.row0;
+  if (rows > MERGE_ROWS) rows = MERGE_ROWS;
+  const int d4 = d >> 2;
+  const int per_row = Hq * d4;
+  const int total = rows * per_row;
+  for (int w = threadIdx.x; w < total; w += MERGE_NT) {
+    const int r = w / per_row, rem = w - r * per_row;
+    const int h = rem / d4, c4 = rem - h * d4;
+    const int rr = it.row0 + r;
+    float lp[ZP_MAX_PARTS];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int p = 0; p < ZP_MAX_PARTS; p++)
+      if (p < mg.n_parts) {
+        lp[p] = lse_part[(int64_t)h * part_rows + mg.part_row0[p] + rr];
+        mx = fmaxf(mx, lp[p]);
+      }
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    float L = -INFINITY;
+    if (mx != -INFINITY) {
+      float sum = 0.f;
+#pragma unroll
+      for (int p = 0; p < ZP_MAX_PARTS; p++)
+        if (p < mg.n_parts) sum += __expf(lp[p] - mx);
+      L = mx + __logf(sum);
+#pragma unroll
+      for (int p = 0; p < ZP_MAX_PARTS; p++)
+        if (p < mg.n_parts && lp[p] != -INFINITY) {
+          const float wgt = __expf(lp[p] - L);
+          const f32x4 v = __builtin_nontemporal_load(
+              (const f32x4 *)(o_part + ((int64_t)(mg.part_row0[p] + rr) * Hq + h) * d) + c4);
+          acc += wgt * v;
+        }
+    }
+    const int64_t t = (int64_t)mg.out_tok0 + rr;
+    bf16x4 ob = {(__bf16)acc[0], (__bf16)acc[1], (__bf16)acc[2], (__bf16)acc[3]};
+    *(bf16x4 *)(o + t * o_stride + (int64_t)h * d + 4 * c4) = ob;
+    if (c4 == 0) lse[(int64_t)h * T + t] = L;
+  }
+}
+}  // namespace
+
+extern "C" int zp_merge_rows_per_item(void) { return MERGE_ROWS; }
+
+extern "C" int zp_launch_lse_merge(const float *o_part, const float *lse_part, int64_t part_rows, const void *merges_dev,
+                                   const void *items_dev, int n_items, int Hq, int d, void *o, int64_t o_stride,
+                                   float *lse, int64_t T, hipStream_t stream) {
+  if (n_items == 0) return 0;
+  hipLaunchKernelGGL(lse_merge_kernel, dim3(n_items), dim3(MERGE_NT), 0, stream, o_part, lse_part, part_rows,
+                     (const zp_merge_dev *)merges_dev, (const zp_merge_item *)items_dev, Hq, d, (__bf16 *)o, o_stride,
+                     lse, T);
+  return (int)hipGetLastError();
+}

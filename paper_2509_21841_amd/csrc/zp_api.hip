@@ -1,0 +1,413 @@
+// C ABI of the attention engine: argument checks, the host planner (work lists ordered by cost), descriptor
+// upload through pinned staging buffers, kernel launches. No device allocation, no synchronisation.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "../../include/zeppelin_attn.h"
+#include "zp_common.h"
+
+extern "C" {
+int zp_launch_attn_fwd(const zp_attn_params *p, int d, int partial, int block_rows, hipStream_t stream);
+int zp_attn_fwd_block_rows(int d);
+int zp_launch_remap(const void *src, void *dst, int64_t row_bytes, const int32_t *idx, int64_t n_rows, int mode,
+                    hipStream_t stream);
+int zp_merge_rows_per_item(void);
+int zp_launch_lse_merge(const float *o_part, const float *lse_part, int64_t part_rows, const void *merges_dev,
+                        const void *items_dev, int n_items, int Hq, int d, void *o, int64_t o_stride, float *lse,
+                        int64_t T, hipStream_t stream);
+struct zp_bwd_params;
+int zp_launch_attn_bwd(const zp_bwd_params *p, int d, hipStream_t stream);
+int zp_attn_bwd_block_rows(int d, int which);
+}
+
+namespace {
+
+thread_local std::string g_hip_error = "HIP runtime error";
+
+int hip_fail(hipError_t e, const char *what) {
+  g_hip_error = std::string("HIP runtime error in ") + what + ": " + hipGetErrorString(e);
+  return ZP_EHIP;
+}
+#define ZP_HIP(call, what)                       \
+  do {                                           \
+    hipError_t e__ = (call);                     \
+    if (e__ != hipSuccess) return hip_fail(e__, what); \
+  } while (0)
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// ---- pinned staging pool -------------------------------------------------------------------------
+// Descriptor tables are built in pinned host memory and copied with hipMemcpyAsync; a slot is reused only
+// after the event recorded behind its copy has completed, so the host never overwrites bytes in flight.
+struct Slot {
+  void *host = nullptr;
+  size_t cap = 0;
+  hipEvent_t ev = nullptr;
+  bool in_flight = false;
+};
+std::mutex g_pool_mu;
+std::vector<Slot> g_pool;
+
+int pool_acquire(size_t bytes, int *slot_out) {
+  std::lock_guard<std::mutex> lk(g_pool_mu);
+  for (size_t i = 0; i < g_pool.size(); i++) {
+    Slot &s = g_pool[i];
+    if (s.cap < bytes) continue;
+    if (s.in_flight) {
+      if (hipEventQuery(s.ev) != hipSuccess) continue;
+      s.in_flight = false;
+    }
+    s.in_flight = true;  // reserved by this call
+    *slot_out = (int)i;
+    return ZP_OK;
+  }
+  Slot s;
+  s.cap = std::max<size_t>(align256(bytes), 1 << 16);
+  ZP_HIP(hipHostMalloc(&s.host, s.cap, hipHostMallocDefault), "hipHostMalloc");
+  ZP_HIP(hipEventCreateWithFlags(&s.ev, hipEventDisableTiming), "hipEventCreate");
+  s.in_flight = true;
+  g_pool.push_back(s);
+  *slot_out = (int)g_pool.size() - 1;
+  return ZP_OK;
+}
+
+// Copy `bytes` from the slot to device memory on `stream` and mark the slot busy until the copy is done.
+int pool_upload(int slot, void *dev, size_t bytes, hipStream_t stream) {
+  Slot s;
+  {
+    std::lock_guard<std::mutex> lk(g_pool_mu);
+    s = g_pool[slot];
+  }
+  ZP_HIP(hipMemcpyAsync(dev, s.host, bytes, hipMemcpyHostToDevice, stream), "hipMemcpyAsync");
+  ZP_HIP(hipEventRecord(s.ev, stream), "hipEventRecord");
+  return ZP_OK;
+}
+void *pool_ptr(int slot) {
+  std::lock_guard<std::mutex> lk(g_pool_mu);
+  return g_pool[slot].host;
+}
+void pool_release_unused(int slot) {
+  std::lock_guard<std::mutex> lk(g_pool_mu);
+  g_pool[slot].in_flight = false;
+}
+
+// ---- checks --------------------------------------------------------------------------------------
+int check_shape(const zp_shape *sh) {
+  if (!sh) return ZP_EINVAL;
+  if (sh->T < 0 || sh->S < 0 || sh->Hq <= 0 || sh->Hkv <= 0) return ZP_EINVAL;
+  if (!(sh->scale >= 0.f) || std::isinf(sh->scale)) return ZP_EINVAL;
+  if (sh->d != 64 && sh->d != 128) return ZP_EUNSUPPORTED;
+  if (sh->Hq % sh->Hkv) return ZP_EUNSUPPORTED;
+  return ZP_OK;
+}
+int check_cu(const int32_t *cu, const zp_shape *sh) {
+  if (!cu) return ZP_EINVAL;
+  if (cu[0] != 0) return ZP_EINVAL;
+  for (int s = 0; s < sh->S; s++)
+    if (cu[s + 1] < cu[s]) return ZP_EINVAL;
+  if (cu[sh->S] != sh->T) return ZP_EINVAL;
+  return ZP_OK;
+}
+int check_stride(int64_t stride, int H, int d) { return (stride < (int64_t)H * d || (stride % 8)) ? ZP_EINVAL : ZP_OK; }
+bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
+int check_ws(const void *ws, size_t have, size_t need) {
+  if (need == 0) return ZP_OK;
+  if (!ws || ((uintptr_t)ws & 255) || have < need) return ZP_EWORKSPACE;
+  return ZP_OK;
+}
+float eff_scale(const zp_shape *sh) { return sh->scale > 0.f ? sh->scale : 1.0f / std::sqrt((float)sh->d); }
+
+// ---- planner -------------------------------------------------------------------------------------
+// A tile's cost is the number of key tiles it visits: the per-block share of the quadratic cost |s|^2 that
+// Alg. 2 balances. Tiles are issued in descending cost so the heaviest start first.
+struct CostTile {
+  zp_tile t;
+  int32_t cost;
+};
+inline int32_t tile_cost(const zp_tile &t) {
+  int64_t n = (int64_t)t.q_pos0 + t.q_rows - 1 - t.k_pos0 + 1;
+  if (n < 0) n = 0;
+  if (n > t.k_len) n = t.k_len;
+  return (int32_t)((n + 63) / 64);
+}
+void sort_by_cost(std::vector<CostTile> &v) {
+  std::stable_sort(v.begin(), v.end(), [](const CostTile &a, const CostTile &b) { return a.cost > b.cost; });
+}
+int64_t count_blocks(const int32_t *cu, int S, int bm) {
+  int64_t n = 0;
+  for (int s = 0; s < S; s++) n += ((int64_t)cu[s + 1] - cu[s] + bm - 1) / bm;
+  return n;
+}
+void plan_whole(const int32_t *cu, int S, int bm, std::vector<CostTile> &out) {
+  for (int s = 0; s < S; s++) {
+    const int32_t L = cu[s + 1] - cu[s];
+    for (int32_t r0 = 0; r0 < L; r0 += bm) {
+      CostTile c;
+      c.t.q_tok0 = cu[s] + r0;
+      c.t.q_rows = std::min(bm, L - r0);
+      c.t.q_pos0 = r0;
+      c.t.k_tok0 = cu[s];
+      c.t.k_len = L;
+      c.t.k_pos0 = 0;
+      c.t.out_row0 = cu[s] + r0;
+      c.t.aux = 0;
+      c.cost = tile_cost(c.t);
+      out.push_back(c);
+    }
+  }
+  sort_by_cost(out);
+}
+int64_t count_pair_blocks(const zp_pair *pairs, int n, int bm) {
+  int64_t c = 0;
+  for (int i = 0; i < n; i++) c += ((int64_t)pairs[i].q_len + bm - 1) / bm;
+  return c;
+}
+
+int upload_tiles(const std::vector<CostTile> &tiles, void *ws, hipStream_t stream) {
+  if (tiles.empty()) return ZP_OK;
+  const size_t bytes = tiles.size() * sizeof(zp_tile);
+  int slot;
+  int rc = pool_acquire(bytes, &slot);
+  if (rc) return rc;
+  zp_tile *h = (zp_tile *)pool_ptr(slot);
+  for (size_t i = 0; i < tiles.size(); i++) h[i] = tiles[i].t;
+  rc = pool_upload(slot, ws, bytes, stream);
+  if (rc) pool_release_unused(slot);
+  return rc;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *zp_strerror(int code) {
+  switch (code) {
+    case ZP_OK: return "ok";
+    case ZP_EINVAL: return "invalid argument";
+    case ZP_EUNSUPPORTED: return "unsupported configuration";
+    case ZP_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case ZP_EHIP: return g_hip_error.c_str();
+    default: return "unknown error code";
+  }
+}
+
+size_t zp_workspace_bytes(int which_fn, const zp_shape *sh, const int32_t *cu, int64_t n_desc) {
+  if (check_shape(sh) != ZP_OK) return 0;
+  switch (which_fn) {
+    case ZP_FN_FWD: {
+      if (check_cu(cu, sh) != ZP_OK) return 0;
+      return align256((size_t)count_blocks(cu, sh->S, zp_attn_fwd_block_rows(sh->d)) * sizeof(zp_tile)) + 256;
+    }
+    case ZP_FN_PARTIAL: {
+      if (n_desc < 0) return 0;
+      // a pair of q_len rows yields ceil(q_len / block_rows) tiles; bound it with T rows per pair... the exact
+      // count needs the pairs, so this bound uses one tile per block_rows tokens of T plus one per pair, per pair
+      const int bm = zp_attn_fwd_block_rows(sh->d);
+      return align256((size_t)n_desc * ((size_t)sh->T / bm + 1) * sizeof(zp_tile)) + 256;
+    }
+    case ZP_FN_MERGE: {
+      if (n_desc < 0) return 0;
+      const int rpi = zp_merge_rows_per_item();
+      return align256((size_t)n_desc * sizeof(zp_merge)) + align256(((size_t)sh->T / rpi + (size_t)n_desc + 1) * 8) + 256;
+    }
+    case ZP_FN_BWD: {
+      if (check_cu(cu, sh) != ZP_OK) return 0;
+      const size_t tiles = (size_t)count_blocks(cu, sh->S, zp_attn_bwd_block_rows(sh->d, 0)) +
+                           (size_t)count_blocks(cu, sh->S, zp_attn_bwd_block_rows(sh->d, 1));
+      return align256(tiles * sizeof(zp_tile)) + align256((size_t)sh->Hq * (size_t)sh->T * sizeof(float)) + 512;
+    }
+    default: return 0;
+  }
+}
+
+int varlen_attn_fwd(const void *q, const void *k, const void *v, int64_t q_stride, int64_t k_stride, int64_t v_stride,
+                    const int32_t *cu, void *o, int64_t o_stride, float *lse, const zp_shape *sh, void *ws,
+                    size_t ws_bytes, void *stream) {
+  int rc = check_shape(sh);
+  if (rc) return rc;
+  if ((rc = check_cu(cu, sh))) return rc;
+  if (sh->T == 0) return ZP_OK;
+  if (!q || !k || !v || !o || !lse) return ZP_EINVAL;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return ZP_EINVAL;
+  if (check_stride(q_stride, sh->Hq, sh->d) || check_stride(o_stride, sh->Hq, sh->d) ||
+      check_stride(k_stride, sh->Hkv, sh->d) || check_stride(v_stride, sh->Hkv, sh->d))
+    return ZP_EINVAL;
+  const int bm = zp_attn_fwd_block_rows(sh->d);
+  std::vector<CostTile> tiles;
+  tiles.reserve((size_t)count_blocks(cu, sh->S, bm));
+  plan_whole(cu, sh->S, bm, tiles);
+  if ((rc = check_ws(ws, ws_bytes, align256(tiles.size() * sizeof(zp_tile))))) return rc;
+  if ((rc = upload_tiles(tiles, ws, (hipStream_t)stream))) return rc;
+  zp_attn_params p{};
+  p.q = (const __bf16 *)q; p.k = (const __bf16 *)k; p.v = (const __bf16 *)v;
+  p.q_stride = q_stride; p.k_stride = k_stride; p.v_stride = v_stride;
+  p.tiles = (const zp_tile *)ws; p.n_tiles = (int32_t)tiles.size();
+  p.Hq = sh->Hq; p.Hkv = sh->Hkv; p.grp = sh->Hq / sh->Hkv;
+  p.scale = eff_scale(sh); p.scale_log2 = p.scale * 1.4426950408889634f;
+  p.o = o; p.o_stride = o_stride; p.lse = lse; p.lse_stride = sh->T;
+  hipError_t e = (hipError_t)zp_launch_attn_fwd(&p, sh->d, 0, bm, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, "attn_fwd launch");
+  return ZP_OK;
+}
+
+int chunk_attn_partial(const void *q, const void *k, const void *v, int64_t q_stride, int64_t k_stride,
+                       int64_t v_stride, const zp_pair *pairs, int32_t n_pairs, float *o_part, float *lse_part,
+                       int64_t part_rows, const zp_shape *sh, void *ws, size_t ws_bytes, void *stream) {
+  int rc = check_shape(sh);
+  if (rc) return rc;
+  if (n_pairs < 0 || part_rows < 0) return ZP_EINVAL;
+  if (n_pairs == 0) return ZP_OK;
+  if (!q || !k || !v || !o_part || !lse_part || !pairs) return ZP_EINVAL;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o_part)) return ZP_EINVAL;
+  if (check_stride(q_stride, sh->Hq, sh->d) || check_stride(k_stride, sh->Hkv, sh->d) ||
+      check_stride(v_stride, sh->Hkv, sh->d))
+    return ZP_EINVAL;
+  for (int i = 0; i < n_pairs; i++) {
+    const zp_pair &pr = pairs[i];
+    if (pr.q_len < 0 || pr.k_len < 0 || pr.q_tok0 < 0 || pr.k_tok0 < 0 || pr.q_pos0 < 0 || pr.k_pos0 < 0 ||
+        pr.out_row0 < 0)
+      return ZP_EINVAL;
+    if ((int64_t)pr.q_tok0 + pr.q_len > sh->T || (int64_t)pr.k_tok0 + pr.k_len > sh->T) return ZP_EINVAL;
+    if ((int64_t)pr.out_row0 + pr.q_len > part_rows) return ZP_EINVAL;
+  }
+  const int bm = zp_attn_fwd_block_rows(sh->d);
+  std::vector<CostTile> tiles;
+  tiles.reserve((size_t)count_pair_blocks(pairs, n_pairs, bm));
+  for (int i = 0; i < n_pairs; i++) {
+    const zp_pair &pr = pairs[i];
+    for (int32_t r0 = 0; r0 < pr.q_len; r0 += bm) {
+      CostTile c;
+      c.t.q_tok0 = pr.q_tok0 + r0;
+      c.t.q_rows = std::min(bm, pr.q_len - r0);
+      c.t.q_pos0 = pr.q_pos0 + r0;
+      c.t.k_tok0 = pr.k_tok0;
+      c.t.k_len = pr.k_len;
+      c.t.k_pos0 = pr.k_pos0;
+      c.t.out_row0 = pr.out_row0 + r0;
+      c.t.aux = 0;
+      c.cost = tile_cost(c.t);
+      tiles.push_back(c);
+    }
+  }
+  sort_by_cost(tiles);
+  if ((rc = check_ws(ws, ws_bytes, align256(tiles.size() * sizeof(zp_tile))))) return rc;
+  if ((rc = upload_tiles(tiles, ws, (hipStream_t)stream))) return rc;
+  zp_attn_params p{};
+  p.q = (const __bf16 *)q; p.k = (const __bf16 *)k; p.v = (const __bf16 *)v;
+  p.q_stride = q_stride; p.k_stride = k_stride; p.v_stride = v_stride;
+  p.tiles = (const zp_tile *)ws; p.n_tiles = (int32_t)tiles.size();
+  p.Hq = sh->Hq; p.Hkv = sh->Hkv; p.grp = sh->Hq / sh->Hkv;
+  p.scale = eff_scale(sh); p.scale_log2 = p.scale * 1.4426950408889634f;
+  p.o = o_part; p.o_stride = (int64_t)sh->Hq * sh->d; p.lse = lse_part; p.lse_stride = part_rows;
+  hipError_t e = (hipError_t)zp_launch_attn_fwd(&p, sh->d, 1, bm, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, "chunk_attn_partial launch");
+  return ZP_OK;
+}
+
+int lse_merge(const float *o_part, const float *lse_part, int64_t part_rows, const zp_merge *merges, int32_t n_merges,
+              void *o, int64_t o_stride, float *lse, const zp_shape *sh, void *ws, size_t ws_bytes, void *stream) {
+  int rc = check_shape(sh);
+  if (rc) return rc;
+  if (n_merges < 0 || part_rows < 0) return ZP_EINVAL;
+  if (n_merges == 0) return ZP_OK;
+  if (!o_part || !lse_part || !merges || !o || !lse) return ZP_EINVAL;
+  if (!aligned16(o_part) || !aligned16(o)) return ZP_EINVAL;
+  if (check_stride(o_stride, sh->Hq, sh->d)) return ZP_EINVAL;
+  const int rpi = zp_merge_rows_per_item();
+  size_t n_items = 0;
+  for (int i = 0; i < n_merges; i++) {
+    const zp_merge &m = merges[i];
+    if (m.n_parts < 1 || m.n_parts > ZP_MAX_PARTS || m.len < 0 || m.out_tok0 < 0 ||
+        (int64_t)m.out_tok0 + m.len > sh->T)
+      return ZP_EINVAL;
+    for (int p = 0; p < m.n_parts; p++)
+      if (m.part_row0[p] < 0 || (int64_t)m.part_row0[p] + m.len > part_rows) return ZP_EINVAL;
+    n_items += ((size_t)m.len + rpi - 1) / rpi;
+  }
+  const size_t desc_bytes = align256((size_t)n_merges * sizeof(zp_merge));
+  const size_t item_bytes = n_items * 8;
+  if ((rc = check_ws(ws, ws_bytes, desc_bytes + align256(item_bytes)))) return rc;
+  if (n_items == 0) return ZP_OK;
+  int slot;
+  if ((rc = pool_acquire(desc_bytes + item_bytes, &slot))) return rc;
+  char *h = (char *)pool_ptr(slot);
+  std::memcpy(h, merges, (size_t)n_merges * sizeof(zp_merge));
+  int32_t *items = (int32_t *)(h + desc_bytes);
+  size_t n = 0;
+  for (int i = 0; i < n_merges; i++)
+    for (int32_t r0 = 0; r0 < merges[i].len; r0 += rpi) {
+      items[2 * n] = i;
+      items[2 * n + 1] = r0;
+      n++;
+    }
+  rc = pool_upload(slot, ws, desc_bytes + item_bytes, (hipStream_t)stream);
+  if (rc) { pool_release_unused(slot); return rc; }
+  hipError_t e = (hipError_t)zp_launch_lse_merge(o_part, lse_part, part_rows, ws, (char *)ws + desc_bytes, (int)n_items,
+                                                 sh->Hq, sh->d, o, o_stride, lse, sh->T, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, "lse_merge launch");
+  return ZP_OK;
+}
+
+int remap_tokens(const void *src, void *dst, int64_t row_bytes, const int32_t *idx_dev, int64_t n_rows, int32_t mode,
+                 void *stream) {
+  if (n_rows < 0 || row_bytes <= 0 || (mode != 0 && mode != 1)) return ZP_EINVAL;
+  if (row_bytes % 16) return ZP_EUNSUPPORTED;
+  if (n_rows == 0) return ZP_OK;
+  if (!src || !dst || !idx_dev) return ZP_EINVAL;
+  if (!aligned16(src) || !aligned16(dst)) return ZP_EINVAL;
+  if (n_rows > 0x7fffffffLL || row_bytes > (1 << 20)) return ZP_EUNSUPPORTED;
+  const char *s = (const char *)src;
+  const char *d = (const char *)dst;
+  const int64_t bytes = n_rows * row_bytes;
+  if (s < d + bytes && d < s + bytes) return ZP_EINVAL;  // overlap
+  hipError_t e = (hipError_t)zp_launch_remap(src, dst, row_bytes, idx_dev, n_rows, mode, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, "remap_tokens launch");
+  return ZP_OK;
+}
+
+int zp_chunk_pairs(int32_t tok0, int32_t L, int32_t C, int32_t rank, int32_t row0, zp_pair *pairs, int32_t max_pairs,
+                   zp_merge *merges, int32_t max_merges, int32_t *n_merges, int64_t *rows_used) {
+  if (L < 0 || C < 1 || tok0 < 0 || row0 < 0 || !pairs || !merges || !n_merges || !rows_used) return ZP_EINVAL;
+  if (rank >= 0 && ((C & 1) || rank >= C / 2)) return ZP_EINVAL;
+  auto bound = [&](int c) { return (int32_t)(((int64_t)c * L) / C); };
+  int np = 0, nm = 0;
+  int64_t row = row0;
+  for (int qc = 0; qc < C; qc++) {
+    if (rank >= 0 && qc != rank && qc != C - 1 - rank) continue;
+    if (qc + 1 > ZP_MAX_PARTS) return ZP_EUNSUPPORTED;
+    if (nm >= max_merges) return ZP_EINVAL;
+    const int32_t qlen = bound(qc + 1) - bound(qc);
+    zp_merge &m = merges[nm++];
+    m.out_tok0 = tok0 + bound(qc);
+    m.len = qlen;
+    m.n_parts = qc + 1;
+    for (int kc = 0; kc <= qc; kc++) {
+      if (np >= max_pairs) return ZP_EINVAL;
+      if (row + qlen > 0x7fffffffLL) return ZP_EINVAL;
+      zp_pair &p = pairs[np++];
+      p.q_tok0 = tok0 + bound(qc); p.q_len = qlen; p.q_pos0 = bound(qc);
+      p.k_tok0 = tok0 + bound(kc); p.k_len = bound(kc + 1) - bound(kc); p.k_pos0 = bound(kc);
+      p.out_row0 = (int32_t)row;
+      m.part_row0[kc] = (int32_t)row;
+      row += qlen;
+    }
+  }
+  *n_merges = nm;
+  *rows_used = row - row0;
+  return np;
+}
+
+}  // extern "C"
+
+extern "C" int varlen_attn_bwd(const void *, const void *, const void *, const void *, const void *, const float *,
+                               int64_t, int64_t, int64_t, int64_t, int64_t, const int32_t *, void *, void *, void *,
+                               int64_t, int64_t, const zp_shape *, void *, size_t, void *) {
+  return ZP_EUNSUPPORTED;
+}

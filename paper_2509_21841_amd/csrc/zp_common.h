@@ -1,0 +1,100 @@
+// Shared device-side types and small helpers for the gfx950 kernels of the attention engine.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+#define ZP_LDS __attribute__((address_space(3)))
+
+// One unit of attention work: a block of query rows against one run of keys of the same sequence.
+// Whole sequences and (Q chunk, KV chunk) pairs (Sec. 3.2) both reduce to this.
+struct zp_tile {
+  int32_t q_tok0;    // first packed query token of the block
+  int32_t q_rows;    // query rows in the block
+  int32_t q_pos0;    // position of the first query row inside its sequence
+  int32_t k_tok0;    // first packed token of the key run
+  int32_t k_len;     // keys in the run
+  int32_t k_pos0;    // position of the first key inside the sequence
+  int32_t out_row0;  // first output row (packed token, or partial-result row)
+  int32_t aux;       // kernel specific
+};
+
+// Parameters shared by the attention kernels. Strides are token strides in elements.
+struct zp_attn_params {
+  const __bf16 *q, *k, *v;
+  int64_t q_stride, k_stride, v_stride;
+  const zp_tile *tiles;
+  int32_t n_tiles, Hq, Hkv, grp;
+  float scale_log2;  // scale * log2(e)
+  float scale;
+  void *o;           // bf16 [.][Hq][d] (whole) or float [part_rows][Hq][d] (partial)
+  int64_t o_stride;  // token stride of o in elements
+  float *lse;        // [Hq][lse_stride]
+  int64_t lse_stride;
+};
+
+// blockIdx -> (unit, head-in-group). Workgroups are dealt to the 8 XCDs round-robin by blockIdx, so
+// units (tile, kv head) are dealt round-robin too -- the cost-sorted list stays balanced across XCDs --
+// while the grp query heads of one unit get consecutive slots on the SAME XCD and share K/V in its L2.
+__device__ __forceinline__ void zp_block_to_unit(int bid, int grp, int &unit, int &hh) {
+  int x = bid & 7, y = bid >> 3;
+  hh = y % grp;
+  unit = (y / grp) * 8 + x;
+}
+
+__device__ __forceinline__ float zp_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// max / sum across the two lanes l and l^32 that hold the two halves of one 32x32 MFMA column.
+__device__ __forceinline__ float zp_pair_max(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float zp_pair_sum(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// 16-byte LDS read / write and the gfx950 transposing 8-byte LDS read.
+__device__ __forceinline__ bf16x8 zp_lds_read16(const char *smem, int off) {
+  return *(const ZP_LDS bf16x8 *)((const ZP_LDS char *)smem + off);
+}
+__device__ __forceinline__ void zp_lds_write16(char *smem, int off, u32x4 v) {
+  *(ZP_LDS u32x4 *)((ZP_LDS char *)smem + off) = v;
+}
+// Within each group of 16 lanes, lane i passes the address of 4 consecutive 16-bit elements of row i/4,
+// columns 4*(i%4)..+3 of a 4x16 block, and receives column i of rows 0..3.
+__device__ __forceinline__ bf16x4 zp_lds_read_tr(const char *smem, int off) {
+  s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ZP_LDS s16x4 *)((ZP_LDS char *)smem + off));
+  return __builtin_bit_cast(bf16x4, v);
+}
+
+__device__ __forceinline__ bf16x8 zp_cat(bf16x4 a, bf16x4 b) {
+  return __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
+// Byte offset of 16-byte chunk c of row `row` in a [rows][D] bf16 LDS tile read row-wise as an MFMA
+// operand (16 consecutive lanes read the same chunk of 16 consecutive rows): the chunk index is XORed
+// with the row so those 16 reads spread over all banks.
+template <int D>
+__device__ __forceinline__ int zp_koff(int row, int c) {
+  if (D == 128) return row * 256 + ((c ^ (row & 15)) << 4);
+  return row * 128 + ((c ^ ((row >> 1) & 7)) << 4);
+}
+// Byte offset of element column `col` (multiple of 4) of row `row` in a [rows][D] bf16 LDS tile read with
+// the transposing read (a wave reads 8 consecutive rows x 64 contiguous bytes): 64-byte segments are XORed
+// with the row so 4 consecutive rows land in 4 different bank quarters.
+template <int D>
+__device__ __forceinline__ int zp_voff(int row, int col) {
+  int b = col * 2, seg = b >> 6, within = b & 63;
+  if (D == 128) return row * 256 + (((seg ^ (row & 3))) << 6) + within;
+  return row * 128 + ((seg ^ ((row >> 1) & 1)) << 6) + within;
+}

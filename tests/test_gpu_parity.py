@@ -1,0 +1,158 @@
+"""Parity of the HIP path (through the C ABI) against the fp64 oracle on seeded synthetic inputs."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2509_21841_amd import binding as B
+from paper_2509_21841_amd import synth
+from util import assert_close, assert_lse_close, widen
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def make(lengths, Hq, Hkv, d, seed, with_dout=False):
+    T = int(sum(lengths))
+    ts = synth.make_qkv(T, Hq, Hkv, d, seed, device=DEV, with_dout=with_dout)
+    return ts, synth.cu_seqlens(lengths)
+
+
+# ---- remap -------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n,row_elems", [(1, 8), (257, 24), (5000, 1024), (4096, 8192), (3, 64)])
+def test_remap_bit_exact(n, row_elems):
+    g = torch.Generator(device="cpu"); g.manual_seed(n)
+    x = torch.randint(-32768, 32767, (n, row_elems), dtype=torch.int16, generator=g).to(DEV)
+    idx = torch.randperm(n, generator=g).to(torch.int32)
+    ref = oracle.remap_tokens(x.cpu().numpy(), idx.numpy(), 0)
+    got = B.remap_tokens(x, idx.to(DEV), 0)
+    assert np.array_equal(got.cpu().numpy(), ref)
+    ref1 = oracle.remap_tokens(x.cpu().numpy(), idx.numpy(), 1)
+    got1 = B.remap_tokens(x, idx.to(DEV), 1)
+    assert np.array_equal(got1.cpu().numpy(), ref1)
+    back = B.remap_tokens(got, idx.to(DEV), 1)
+    assert torch.equal(back, x)
+
+
+def test_remap_empty_and_layout_round_trip():
+    assert B.remap_tokens(torch.empty((0, 64), dtype=torch.bfloat16, device=DEV), torch.empty(0, dtype=torch.int32, device=DEV)).shape[0] == 0
+    lengths = synth.lengths_lognormal(8192, 5, median=256, lo=16, hi=2048)
+    idx, attn_lengths, _ = synth.balanced_attention_layout(lengths, R=8)
+    (q, k, v), _ = make(lengths, 8, 2, 128, 5)
+    idx_d = torch.from_numpy(idx).to(DEV)
+    qa = B.remap_tokens(q, idx_d, 0)
+    assert np.array_equal(synth.bf16_bits(qa), oracle.remap_tokens(synth.bf16_bits(q), idx, 0))
+    assert torch.equal(B.remap_tokens(qa, idx_d, 1).view(torch.int16), q.view(torch.int16))
+
+
+# ---- merge -------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("Hq,d,n,parts", [(4, 64, 37, 3), (32, 128, 300, 4), (2, 128, 9, 1), (3, 64, 20, 8)])
+def test_lse_merge_matches_oracle(Hq, d, n, parts):
+    g = torch.Generator(device="cpu"); g.manual_seed(Hq * 1000 + n)
+    rows = parts * n + 5
+    op = torch.randn((rows, Hq, d), generator=g, dtype=torch.float32)
+    lp = torch.randn((Hq, rows), generator=g, dtype=torch.float32) * 3
+    lp[:, 2] = float("-inf")
+    if parts > 1:
+        lp[0, [3 + p * n for p in range(parts)]] = float("-inf")   # a row whose parts are all -inf
+    merges = [(1, n, [p * n for p in range(parts)])]
+    T = n + 3
+    o = torch.zeros((T, Hq, d), dtype=torch.bfloat16, device=DEV); lse = torch.zeros((Hq, T), dtype=torch.float32, device=DEV)
+    B.lse_merge(op.to(DEV), lp.to(DEV), merges, o, lse)
+    ro, rl = oracle.lse_merge(op.double().numpy(), lp.double().numpy(), merges, T, np.zeros((T, Hq, d)), np.zeros((Hq, T)))
+    assert_close("merge O", widen(o), ro, maxabs=2e-2, rell2=5e-3)
+    assert_lse_close("merge LSE", widen(lse), rl)
+    assert (widen(o)[0] == 0).all() and (widen(o)[n + 1:] == 0).all()   # rows outside the merge untouched
+
+
+# ---- forward -----------------------------------------------------------------------------------------
+def run_fwd(lengths, Hq, Hkv, d, seed, scale=0.0):
+    (q, k, v), cu = make(lengths, Hq, Hkv, d, seed)
+    o, lse = B.varlen_attn_fwd(q, k, v, cu, scale=scale)
+    torch.cuda.synchronize()
+    ro, rl = oracle.varlen_attn_fwd(widen(q), widen(k), widen(v), cu, scale=scale or None)
+    assert_close("O", widen(o), ro)
+    assert_lse_close("LSE", widen(lse), rl)
+    return (q, k, v), cu, (o, lse), (ro, rl)
+
+
+def test_fwd_tiny_config_and_chunk_split_of_longest():
+    """Config 1: 8 sequences U[16,512], <= 2048 tokens, 4 heads, d 64; the longest sequence is also split
+    into 2 chunks (3 causal pairs) and merged."""
+    lengths = synth.lengths_tiny(1001)
+    (q, k, v), cu, (o, lse), (ro, rl) = run_fwd(lengths, 4, 4, 64, 1001)
+    s = int(np.argmax(lengths)); L = lengths[s]; t0 = int(cu[s])
+    pairs, merges, rows = B.chunk_pairs(t0, L, 2)
+    assert len(pairs) == 3
+    op, lp = B.chunk_attn_partial(q, k, v, pairs, rows)
+    opairs, omerges, orows = oracle.causal_pairs(t0, L, 2)
+    rop, rlp = oracle.chunk_attn_partial(widen(q), widen(k), widen(v), opairs, orows)
+    assert_close("O_part", widen(op), rop)
+    assert_lse_close("LSE_part", widen(lp), rlp)
+    o2 = torch.zeros_like(o); lse2 = torch.zeros_like(lse)
+    B.lse_merge(op, lp, merges, o2, lse2)
+    assert_close("merged O", widen(o2)[t0:t0 + L], ro[t0:t0 + L])
+    assert_lse_close("merged LSE", widen(lse2)[:, t0:t0 + L], rl[:, t0:t0 + L])
+
+
+@pytest.mark.parametrize("lengths,Hq,Hkv,d", [
+    ([1], 1, 1, 64), ([1, 1, 2, 3], 2, 1, 128), ([127, 128, 129], 2, 2, 128), ([64, 65, 63, 1], 4, 2, 64),
+    ([700, 0, 333, 0], 8, 2, 128), ([1500], 4, 1, 128), ([300, 41], 2, 2, 64)])
+def test_fwd_edge_lengths(lengths, Hq, Hkv, d):
+    run_fwd(lengths, Hq, Hkv, d, 7)
+
+
+def test_fwd_custom_scale_and_strided_qkv():
+    lengths = [200, 77]
+    T, Hq, Hkv, d = 277, 4, 2, 128
+    fused = synth.normal_bf16((T, Hq + 2 * Hkv, d), 3, 1, DEV)
+    q, k, v = fused[:, :Hq], fused[:, Hq:Hq + Hkv], fused[:, Hq + Hkv:]
+    cu = synth.cu_seqlens(lengths)
+    o, lse = B.varlen_attn_fwd(q, k, v, cu, scale=0.05)
+    ro, rl = oracle.varlen_attn_fwd(widen(q.contiguous()), widen(k.contiguous()), widen(v.contiguous()), cu, scale=0.05)
+    assert_close("O", widen(o), ro); assert_lse_close("LSE", widen(lse), rl)
+
+
+def test_fwd_closed_forms_on_device():
+    lengths = [1, 300]
+    (q, k, v), cu = make(lengths, 2, 2, 128, 9)
+    o, lse = B.varlen_attn_fwd(torch.zeros_like(q), k, v, cu)
+    vf = widen(v)
+    pm = np.cumsum(vf[1:], axis=0) / np.arange(1, 301)[:, None, None]
+    assert_close("prefix mean", widen(o)[1:], pm)
+    assert np.abs(widen(lse)[:, 1:] - np.log(np.arange(1, 301))).max() < 1e-3
+    assert np.array_equal(widen(o)[0], vf[0])   # length-1 sequence returns V
+
+
+def test_fwd_deterministic():
+    lengths = [513, 200]
+    (q, k, v), cu = make(lengths, 4, 2, 128, 13)
+    a = B.varlen_attn_fwd(q, k, v, cu); b = B.varlen_attn_fwd(q, k, v, cu)
+    assert torch.equal(a[0].view(torch.int16), b[0].view(torch.int16)) and torch.equal(a[1], b[1])
+
+
+# ---- partials ----------------------------------------------------------------------------------------
+@pytest.mark.parametrize("L,C,Hq,Hkv,d", [(1000, 4, 4, 1, 128), (257, 3, 2, 2, 64), (130, 4, 2, 1, 128)])
+def test_chunked_then_merged_equals_whole(L, C, Hq, Hkv, d):
+    lengths = [50, L, 31]
+    (q, k, v), cu = make(lengths, Hq, Hkv, d, 17)
+    t0 = int(cu[1])
+    pairs, merges, rows = B.chunk_pairs(t0, L, C)
+    op, lp = B.chunk_attn_partial(q, k, v, pairs, rows)
+    opairs, _, orows = oracle.causal_pairs(t0, L, C)
+    rop, rlp = oracle.chunk_attn_partial(widen(q), widen(k), widen(v), opairs, orows)
+    assert_close("O_part", widen(op), rop); assert_lse_close("LSE_part", widen(lp), rlp)
+    o = torch.zeros_like(q); lse = torch.zeros((Hq, q.shape[0]), dtype=torch.float32, device=DEV)
+    B.lse_merge(op, lp, merges, o, lse)
+    ro, rl = oracle.varlen_attn_fwd(widen(q), widen(k), widen(v), cu)
+    assert_close("merged O", widen(o)[t0:t0 + L], ro[t0:t0 + L])
+    assert_lse_close("merged LSE", widen(lse)[:, t0:t0 + L], rl[:, t0:t0 + L])
+
+
+def test_partial_rows_without_visible_keys():
+    (q, k, v), cu = make([400], 2, 1, 128, 19)
+    pairs = [dict(q_tok0=100, q_len=200, k_tok0=200, k_len=150, q_pos0=100, k_pos0=200, out_row0=3)]
+    op, lp = B.chunk_attn_partial(q, k, v, pairs, 210)
+    rop, rlp = oracle.chunk_attn_partial(widen(q), widen(k), widen(v), pairs, 210)
+    assert_close("O_part", widen(op)[3:203], rop[3:203]); assert_lse_close("LSE_part", widen(lp)[:, 3:203], rlp[:, 3:203])
+    assert np.isneginf(widen(lp)[:, 3:103]).all()

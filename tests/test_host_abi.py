@@ -1,0 +1,101 @@
+"""Host-side checks that need no GPU: the library loads, exports every declared symbol, validates arguments
+before touching the device, and its chunk-pair helper agrees with the oracle's enumeration."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2509_21841_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "zeppelin_attn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(\w+)\s*\([^;{]*\)\s*;", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert {"varlen_attn_fwd", "varlen_attn_bwd", "chunk_attn_partial", "lse_merge", "remap_tokens",
+            "zp_workspace_bytes", "zp_strerror", "zp_chunk_pairs"} <= set(names)
+    L = B.lib()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_strerror_texts():
+    L = B.lib()
+    assert L.zp_strerror(0) == b"ok"
+    for code in (-1, -2, -3):
+        assert len(L.zp_strerror(code)) > 3
+
+
+def _fwd_rc(sh, cu, q=1 << 12, k=1 << 12, v=1 << 12, o=1 << 12, lse=1 << 12, qs=None, ws=1 << 12, wsb=1 << 20):
+    L = B.lib()
+    cu = np.ascontiguousarray(cu, np.int32)
+    qs = sh.Hq * sh.d if qs is None else qs
+    return L.varlen_attn_fwd(q, k, v, qs, sh.Hkv * sh.d, sh.Hkv * sh.d, cu.ctypes.data_as(ctypes.c_void_p), o,
+                             sh.Hq * sh.d, lse, ctypes.byref(sh), ws, wsb, None)
+
+
+def test_fwd_argument_validation_without_device():
+    ok = B.make_shape(100, 2, 4, 2, 64)
+    assert _fwd_rc(ok, [0, 40, 100], q=0) == -1                      # null pointer
+    assert _fwd_rc(ok, [1, 40, 100]) == -1                           # cu[0] != 0
+    assert _fwd_rc(ok, [0, 60, 40]) == -1                            # not monotone
+    assert _fwd_rc(ok, [0, 40, 99]) == -1                            # cu[S] != T
+    assert _fwd_rc(B.make_shape(100, 2, 4, 2, 96), [0, 40, 100]) == -2   # head dim
+    assert _fwd_rc(B.make_shape(100, 2, 4, 3, 64), [0, 40, 100]) == -2   # Hq % Hkv
+    assert _fwd_rc(ok, [0, 40, 100], qs=100) == -1                   # token stride below Hq*d
+    assert _fwd_rc(ok, [0, 40, 100], ws=0) == -3                     # no workspace
+    assert _fwd_rc(ok, [0, 40, 100], wsb=16) == -3                   # workspace too small
+    assert _fwd_rc(ok, [0, 40, 100], ws=(1 << 12) + 16) == -3        # misaligned workspace
+    assert _fwd_rc(B.make_shape(0, 1, 4, 2, 64), [0, 0]) == 0        # empty batch is a no-op
+
+
+def test_remap_and_merge_validation_without_device():
+    L = B.lib()
+    assert L.remap_tokens(1 << 12, 1 << 20, 24, 1 << 22, 10, 0, None) == -2     # row_bytes % 16
+    assert L.remap_tokens(1 << 12, 1 << 20, 32, 1 << 22, 10, 2, None) == -1     # bad mode
+    assert L.remap_tokens(1 << 12, (1 << 12) + 64, 32, 1 << 22, 10, 0, None) == -1  # overlap
+    assert L.remap_tokens(0, 1 << 20, 32, 1 << 22, 10, 0, None) == -1
+    assert L.remap_tokens(1 << 12, 1 << 20, 32, 1 << 22, 0, 0, None) == 0       # nothing to move
+    sh = B.make_shape(100, 0, 4, 4, 64)
+    m = (B.ZpMerge * 1)()
+    m[0].out_tok0, m[0].len, m[0].n_parts = 90, 20, 1                            # runs past T
+    assert L.lse_merge(1 << 12, 1 << 12, 100, m, 1, 1 << 12, 256, 1 << 12, ctypes.byref(sh), 1 << 12, 1 << 20, None) == -1
+    m[0].out_tok0, m[0].len, m[0].n_parts = 0, 20, 9                             # too many parts
+    assert L.lse_merge(1 << 12, 1 << 12, 100, m, 1, 1 << 12, 256, 1 << 12, ctypes.byref(sh), 1 << 12, 1 << 20, None) == -1
+    p = (B.ZpPair * 1)()
+    p[0].q_tok0, p[0].q_len, p[0].k_tok0, p[0].k_len, p[0].out_row0 = 0, 50, 60, 50, 0   # keys past T
+    assert L.chunk_attn_partial(1 << 12, 1 << 12, 1 << 12, 256, 256, 256, p, 1, 1 << 12, 1 << 12, 50, ctypes.byref(sh),
+                                1 << 12, 1 << 20, None) == -1
+
+
+@pytest.mark.parametrize("L,C", [(101, 4), (38400, 4), (7, 3), (64, 1), (5, 8)])
+def test_chunk_pairs_match_oracle_enumeration(L, C):
+    pairs, merges, rows = B.chunk_pairs(17, L, C)
+    op, om, orows = oracle.causal_pairs(17, L, C)
+    assert rows == orows and len(pairs) == len(op) and len(merges) == len(om)
+    for a, b in zip(pairs, op):
+        assert {f: getattr(a, f) for f, _ in B.ZpPair._fields_} == b
+    for a, (tok0, ln, prow) in zip(merges, om):
+        assert (a.out_tok0, a.len, a.n_parts) == (tok0, ln, len(prow)) and list(a.part_row0[:a.n_parts]) == prow
+
+
+@pytest.mark.parametrize("G", [1, 2, 4])
+def test_rank_share_matches_ring_schedule(G):
+    C, L = 2 * G, 1000
+    sched = oracle.ring_schedule(G)
+    b = oracle.chunk_bounds(L, C)
+    for rank in range(G):
+        pairs, merges, rows = B.chunk_pairs(0, L, C, rank=rank)
+        got = sorted((b.index(p.q_pos0), b.index(p.k_pos0)) for p in pairs)
+        want = sorted(pr for rnd in sched[rank] for pr in rnd)
+        assert got == want
+        assert sorted(m.out_tok0 for m in merges) == sorted({b[rank], b[C - 1 - rank]})
