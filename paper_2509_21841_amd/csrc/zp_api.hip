@@ -22,7 +22,18 @@ int zp_merge_rows_per_item(void);
 int zp_launch_lse_merge(const float *o_part, const float *lse_part, int64_t part_rows, const void *merges_dev,
                         const void *items_dev, int n_items, int Hq, int d, void *o, int64_t o_stride, float *lse,
                         int64_t T, hipStream_t stream);
-struct zp_bwd_params;
+struct zp_bwd_params {
+  const __bf16 *q, *k, *v, *o, *dout;
+  int64_t q_stride, k_stride, v_stride, o_stride, do_stride;
+  const float *lse;
+  float *dvec;
+  const zp_tile *dq_tiles;
+  const zp_tile *kv_tiles;
+  int32_t n_dq_tiles, n_kv_tiles, Hq, Hkv, grp, T;
+  float scale_log2, scale;
+  __bf16 *dq, *dk, *dv;
+  int64_t dq_stride, dkv_stride;
+};
 int zp_launch_attn_bwd(const zp_bwd_params *p, int d, hipStream_t stream);
 int zp_attn_bwd_block_rows(int d, int which);
 }
@@ -406,8 +417,66 @@ int zp_chunk_pairs(int32_t tok0, int32_t L, int32_t C, int32_t rank, int32_t row
 
 }  // extern "C"
 
-extern "C" int varlen_attn_bwd(const void *, const void *, const void *, const void *, const void *, const float *,
-                               int64_t, int64_t, int64_t, int64_t, int64_t, const int32_t *, void *, void *, void *,
-                               int64_t, int64_t, const zp_shape *, void *, size_t, void *) {
-  return ZP_EUNSUPPORTED;
+extern "C" int varlen_attn_bwd(const void *dout, const void *q, const void *k, const void *v, const void *o,
+                               const float *lse, int64_t do_stride, int64_t q_stride, int64_t k_stride,
+                               int64_t v_stride, int64_t o_stride, const int32_t *cu, void *dq, void *dk, void *dv,
+                               int64_t dq_stride, int64_t dkv_stride, const zp_shape *sh, void *ws, size_t ws_bytes,
+                               void *stream) {
+  int rc = check_shape(sh);
+  if (rc) return rc;
+  if ((rc = check_cu(cu, sh))) return rc;
+  if (sh->T == 0) return ZP_OK;
+  if (!dout || !q || !k || !v || !o || !lse || !dq || !dk || !dv) return ZP_EINVAL;
+  if (!aligned16(dout) || !aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(dq) ||
+      !aligned16(dk) || !aligned16(dv))
+    return ZP_EINVAL;
+  if (check_stride(q_stride, sh->Hq, sh->d) || check_stride(o_stride, sh->Hq, sh->d) ||
+      check_stride(do_stride, sh->Hq, sh->d) || check_stride(dq_stride, sh->Hq, sh->d) ||
+      check_stride(k_stride, sh->Hkv, sh->d) || check_stride(v_stride, sh->Hkv, sh->d) ||
+      check_stride(dkv_stride, sh->Hkv, sh->d))
+    return ZP_EINVAL;
+  const int bmq = zp_attn_bwd_block_rows(sh->d, 0), bnk = zp_attn_bwd_block_rows(sh->d, 1);
+  std::vector<CostTile> qt, kt;
+  qt.reserve((size_t)count_blocks(cu, sh->S, bmq));
+  plan_whole(cu, sh->S, bmq, qt);
+  kt.reserve((size_t)count_blocks(cu, sh->S, bnk));
+  for (int s = 0; s < sh->S; s++) {
+    const int32_t L = cu[s + 1] - cu[s];
+    for (int32_t j0 = 0; j0 < L; j0 += bnk) {
+      CostTile c;
+      c.t.k_tok0 = cu[s] + j0;
+      c.t.k_len = std::min(bnk, L - j0);
+      c.t.k_pos0 = j0;
+      c.t.q_tok0 = cu[s] + j0;  // first query that sees the block's first key
+      c.t.q_rows = L - j0;
+      c.t.q_pos0 = j0;
+      c.t.out_row0 = cu[s] + j0;
+      c.t.aux = 0;
+      c.cost = (c.t.q_rows + 63) / 64;
+      kt.push_back(c);
+    }
+  }
+  sort_by_cost(kt);
+  const size_t tile_bytes = align256((qt.size() + kt.size()) * sizeof(zp_tile));
+  const size_t dvec_bytes = align256((size_t)sh->Hq * (size_t)sh->T * sizeof(float));
+  if ((rc = check_ws(ws, ws_bytes, tile_bytes + dvec_bytes))) return rc;
+  std::vector<CostTile> all(qt);
+  all.insert(all.end(), kt.begin(), kt.end());
+  if ((rc = upload_tiles(all, ws, (hipStream_t)stream))) return rc;
+  zp_bwd_params p{};
+  p.q = (const __bf16 *)q; p.k = (const __bf16 *)k; p.v = (const __bf16 *)v; p.o = (const __bf16 *)o;
+  p.dout = (const __bf16 *)dout;
+  p.q_stride = q_stride; p.k_stride = k_stride; p.v_stride = v_stride; p.o_stride = o_stride; p.do_stride = do_stride;
+  p.lse = lse;
+  p.dvec = (float *)((char *)ws + tile_bytes);
+  p.dq_tiles = (const zp_tile *)ws;
+  p.kv_tiles = (const zp_tile *)ws + qt.size();
+  p.n_dq_tiles = (int32_t)qt.size(); p.n_kv_tiles = (int32_t)kt.size();
+  p.Hq = sh->Hq; p.Hkv = sh->Hkv; p.grp = sh->Hq / sh->Hkv; p.T = sh->T;
+  p.scale = eff_scale(sh); p.scale_log2 = p.scale * 1.4426950408889634f;
+  p.dq = (__bf16 *)dq; p.dk = (__bf16 *)dk; p.dv = (__bf16 *)dv;
+  p.dq_stride = dq_stride; p.dkv_stride = dkv_stride;
+  hipError_t e = (hipError_t)zp_launch_attn_bwd(&p, sh->d, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, "attn_bwd launch");
+  return ZP_OK;
 }

@@ -98,3 +98,18 @@ __device__ __forceinline__ int zp_voff(int row, int col) {
   if (D == 128) return row * 256 + (((seg ^ (row & 3))) << 6) + within;
   return row * 128 + ((seg ^ ((row >> 1) & 1)) << 6) + within;
 }
+
+// Swizzle for LDS tiles that are read BOTH row-wise (16 lanes: 16 consecutive rows, same 16-byte chunk) and
+// with the transposing read (32 lanes: 4 consecutive rows x 64 contiguous bytes): the 16-byte chunk index is
+// XORed with the row's low four bits with their two 2-bit fields swapped, which spreads both patterns over
+// all banks. `chunk` is the 16-byte chunk index in the row; returns the byte offset of that chunk.
+template <int D>
+__device__ __forceinline__ int zp_swz(int row, int chunk) {
+  if (D == 128) return row * 256 + ((chunk ^ (((row & 3) << 2) | ((row >> 2) & 3))) << 4);
+  return row * 128 + ((chunk ^ (((row & 1) << 2) | ((row >> 1) & 3))) << 4);
+}
+// Byte offset of element column `col` (multiple of 4) of row `row` under zp_swz.
+template <int D>
+__device__ __forceinline__ int zp_swz_col(int row, int col) {
+  return zp_swz<D>(row, col >> 3) + ((col & 7) << 1);
+}

@@ -156,3 +156,33 @@ def test_partial_rows_without_visible_keys():
     rop, rlp = oracle.chunk_attn_partial(widen(q), widen(k), widen(v), pairs, 210)
     assert_close("O_part", widen(op)[3:203], rop[3:203]); assert_lse_close("LSE_part", widen(lp)[:, 3:203], rlp[:, 3:203])
     assert np.isneginf(widen(lp)[:, 3:103]).all()
+
+
+# ---- backward ----------------------------------------------------------------------------------------
+def run_bwd(lengths, Hq, Hkv, d, seed, scale=0.0):
+    (q, k, v, do), cu = make(lengths, Hq, Hkv, d, seed, with_dout=True)
+    o, lse = B.varlen_attn_fwd(q, k, v, cu, scale=scale)
+    dq, dk, dv = B.varlen_attn_bwd(do, q, k, v, o, lse, cu, scale=scale)
+    torch.cuda.synchronize()
+    rdq, rdk, rdv = oracle.varlen_attn_bwd(widen(do), widen(q), widen(k), widen(v), cu, scale=scale or None)
+    assert_close("dQ", widen(dq), rdq); assert_close("dK", widen(dk), rdk); assert_close("dV", widen(dv), rdv)
+
+
+def test_bwd_tiny_config():
+    run_bwd(synth.lengths_tiny(1001), 4, 4, 64, 1001)
+
+
+@pytest.mark.parametrize("lengths,Hq,Hkv,d", [
+    ([1], 1, 1, 64), ([1, 1, 2, 3], 2, 1, 128), ([127, 128, 129], 2, 2, 128), ([64, 65, 63, 1], 4, 2, 64),
+    ([700, 0, 333, 0], 8, 2, 128), ([900], 4, 1, 128), ([300, 41], 2, 2, 64)])
+def test_bwd_edge_lengths(lengths, Hq, Hkv, d):
+    run_bwd(lengths, Hq, Hkv, d, 23)
+
+
+def test_bwd_custom_scale_and_deterministic():
+    run_bwd([260, 100], 4, 2, 128, 29, scale=0.05)
+    (q, k, v, do), cu = make([513, 200], 4, 2, 128, 31, with_dout=True)
+    o, lse = B.varlen_attn_fwd(q, k, v, cu)
+    a = B.varlen_attn_bwd(do, q, k, v, o, lse, cu); b = B.varlen_attn_bwd(do, q, k, v, o, lse, cu)
+    for x, y in zip(a, b):
+        assert torch.equal(x.view(torch.int16), y.view(torch.int16))
