@@ -1,0 +1,244 @@
+#!/usr/bin/env python3
+"""Benchmark of the attention engine's whole hot path on one MI355X.
+
+One step = one pass of every stage over one seeded synthetic batch, inputs resident in HBM:
+  remap(Q,K,V: linear -> attention layout) -> forward (short sequences whole, long sequences as 4-chunk
+  causal pairs + LSE merge) -> remap^-1(O) -> remap(dO) -> backward -> remap^-1(dQ,dK,dV).
+Prints ONE JSON line: whole-job causal TFLOP/s (masked pairs not counted; fwd 4*d*Hq*pairs, bwd 10*d*Hq*pairs),
+the roofline of the dominant kernel (per-kernel durations from hipEvents the library records on the launch
+stream) and the fp64 CPU oracle timed on a bounded sample of the same batch.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2509_21841_amd import binding as B  # noqa: E402
+from paper_2509_21841_amd import synth  # noqa: E402
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
+HBM_PEAK_GBPS = 8000.0
+
+WORKLOADS = {
+    # name: (T, Hq, Hkv, d, seed, length recipe, chunks for long sequences, backward?, remap?)
+    "longtail-128k-gqa32x8": dict(T=131072, Hq=32, Hkv=8, d=128, seed=1003, mix="longtail", C=4, bwd=True, remap=True),
+    "lognormal-64k-mha32": dict(T=65536, Hq=32, Hkv=32, d=128, seed=1002, mix="lognormal", C=0, bwd=True, remap=False),
+    "lognormal-256k-gqa64x8": dict(T=262144, Hq=64, Hkv=8, d=128, seed=1005, mix="lognormal", C=0, bwd=True, remap=True),
+}
+
+
+def pairs_of(lengths):
+    return int(sum(L * (L + 1) // 2 for L in lengths))
+
+
+class Job:
+    """All device buffers and descriptors of one workload; step() enqueues the whole hot path once."""
+
+    def __init__(self, name, dev):
+        w = WORKLOADS[name]
+        self.name, self.w, self.dev = name, w, dev
+        T, Hq, Hkv, d = w["T"], w["Hq"], w["Hkv"], w["d"]
+        if w["mix"] == "longtail":
+            lin_lengths, _ = synth.lengths_longtail(T, w["seed"])
+        else:
+            lin_lengths = synth.lengths_lognormal(T, w["seed"])
+        self.lin_lengths = lin_lengths
+        if w["remap"]:
+            idx, attn_lengths, order = synth.balanced_attention_layout(lin_lengths, R=8)
+        else:
+            idx, attn_lengths, order = None, list(lin_lengths), list(range(len(lin_lengths)))
+        self.lengths = attn_lengths
+        self.cu = synth.cu_seqlens(attn_lengths)
+        self.idx = None if idx is None else torch.from_numpy(idx).to(dev)
+        # linear-layout inputs (what the linear modules hand over)
+        self.q_lin, self.k_lin, self.v_lin, self.do_lin = synth.make_qkv(T, Hq, Hkv, d, w["seed"], dev, with_dout=True)
+        e = lambda t: torch.empty_like(t)
+        if w["remap"]:
+            self.q, self.k, self.v, self.do = e(self.q_lin), e(self.k_lin), e(self.v_lin), e(self.do_lin)
+            self.o_lin, self.dq_lin, self.dk_lin, self.dv_lin = e(self.q_lin), e(self.q_lin), e(self.k_lin), e(self.v_lin)
+        else:
+            self.q, self.k, self.v, self.do = self.q_lin, self.k_lin, self.v_lin, self.do_lin
+        self.o = e(self.q)
+        self.lse = torch.empty((Hq, T), dtype=torch.float32, device=dev)
+        self.dq, self.dk, self.dv = e(self.q), e(self.k), e(self.v)
+        # long sequences -> chunk pairs
+        self.skip = np.zeros(len(attn_lengths), np.uint8)
+        pairs, merges, rows = [], [], 0
+        if w["C"]:
+            for s, L in enumerate(attn_lengths):
+                if L >= 16384:
+                    self.skip[s] = 1
+                    p, m, r = B.chunk_pairs(int(self.cu[s]), L, w["C"], row0=rows)
+                    pairs += list(p); merges += list(m); rows += r
+        self.n_long = int(self.skip.sum())
+        self.pairs = (B.ZpPair * len(pairs))(*pairs) if pairs else None
+        self.n_pairs = len(pairs)
+        self.merges = (B.ZpMerge * len(merges))(*merges) if merges else None
+        self.n_merges = len(merges)
+        self.part_rows = rows
+        if rows:
+            self.o_part = torch.empty((rows, Hq, d), dtype=torch.float32, device=dev)
+            self.lse_part = torch.empty((Hq, rows), dtype=torch.float32, device=dev)
+        self.pairs_total = pairs_of(attn_lengths)
+        self.pairs_long = pairs_of([L for L, s in zip(attn_lengths, self.skip) if s])
+        self.flops_fwd = 4 * d * Hq * self.pairs_total
+        self.flops_bwd = 10 * d * Hq * self.pairs_total if w["bwd"] else 0
+        self.merge_bytes = sum(m.len * Hq * (m.n_parts * (4 * d + 4) + 2 * d + 4) for m in merges)
+        rb = lambda t: 2 * t.numel() * 2 + 4 * T
+        self.remap_bytes = 4 * rb(self.q) + 4 * rb(self.k) if w["remap"] else 0  # Q,O,dO,dQ and K,V,dK,dV
+
+    def step(self):
+        w = self.w
+        if w["remap"]:
+            B.remap_tokens(self.q_lin, self.idx, 0, dst=self.q)
+            B.remap_tokens(self.k_lin, self.idx, 0, dst=self.k)
+            B.remap_tokens(self.v_lin, self.idx, 0, dst=self.v)
+        B.varlen_attn_fwd(self.q, self.k, self.v, self.cu, o=self.o, lse=self.lse, seq_skip=self.skip if self.n_long else None)
+        if self.n_pairs:
+            B.chunk_attn_partial(self.q, self.k, self.v, self.pairs, self.part_rows,
+                                 o_part=self.o_part, lse_part=self.lse_part)
+            B.lse_merge(self.o_part, self.lse_part, self.merges, self.o, self.lse)
+        if w["remap"]:
+            B.remap_tokens(self.o, self.idx, 1, dst=self.o_lin)
+        if w["bwd"]:
+            if w["remap"]:
+                B.remap_tokens(self.do_lin, self.idx, 0, dst=self.do)
+            B.varlen_attn_bwd(self.do, self.q, self.k, self.v, self.o, self.lse, self.cu, dq=self.dq, dk=self.dk, dv=self.dv)
+            if w["remap"]:
+                B.remap_tokens(self.dq, self.idx, 1, dst=self.dq_lin)
+                B.remap_tokens(self.dk, self.idx, 1, dst=self.dk_lin)
+                B.remap_tokens(self.dv, self.idx, 1, dst=self.dv_lin)
+
+
+def kernel_flops(job: Job, label: str) -> float:
+    """Algorithmic FLOPs one launch of a kernel performs (2 FLOP per multiply-add over unmasked pairs)."""
+    d, Hq = job.w["d"], job.w["Hq"]
+    per_gemm_all = 2 * d * Hq * job.pairs_total
+    per_gemm_long = 2 * d * Hq * job.pairs_long
+    return {"attn_fwd": 2 * (per_gemm_all - per_gemm_long), "attn_fwd_partial": 2 * per_gemm_long,
+            "attn_bwd_dq": 3 * per_gemm_all, "attn_bwd_dkdv": 4 * per_gemm_all}.get(label, 0.0)
+
+
+def cpu_baseline(job: Job, target_s: float = 15.0):
+    """Times the fp64 oracle (forward + backward, as it stands) on the shortest sequences of the batch."""
+    import oracle
+    d, Hq, Hkv = job.w["d"], job.w["Hq"], job.w["Hkv"]
+    grp = Hq // Hkv
+    order = sorted(range(len(job.lengths)), key=lambda s: job.lengths[s])
+    heads = list(range(grp))  # the query heads of KV group 0
+
+    def run(seqs):
+        toks = np.concatenate([np.arange(job.cu[s], job.cu[s + 1]) for s in seqs])
+        ti = torch.from_numpy(toks).to(job.dev)
+        f = lambda t, hs: oracle.bf16_bits_to_f64(synth.bf16_bits(t[ti][:, hs]))
+        q, do = f(job.q, heads), f(job.do, heads)
+        k, v = f(job.k, [0]), f(job.v, [0])
+        cu = synth.cu_seqlens([job.lengths[s] for s in seqs])
+        t0 = time.perf_counter()
+        oracle.varlen_attn_fwd(q, k, v, cu)
+        oracle.varlen_attn_bwd(do, q, k, v, cu)
+        dt = time.perf_counter() - t0
+        fl = 14 * d * len(heads) * pairs_of([job.lengths[s] for s in seqs])
+        return dt, fl
+
+    dt, fl = run(order[:1])
+    rate = fl / max(dt, 1e-6)
+    chosen, acc = [], 0.0
+    for s in order:
+        f = 14 * d * len(heads) * pairs_of([job.lengths[s]])
+        if chosen and (acc + f) / rate > target_s:
+            break
+        chosen.append(s); acc += f
+    dt, fl = run(chosen)
+    return {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"fp64 oracle fwd+bwd on the {len(chosen)} shortest sequences ({sum(job.lengths[s] for s in chosen)} tokens), "
+                      f"{len(heads)} query heads of KV group 0, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="longtail-128k-gqa32x8", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    B.lib()
+    job = Job(a.workload, dev)
+    for _ in range(a.warmup):
+        job.step()
+    torch.cuda.synchronize()
+    B.profile_enable(True)
+    stream = torch.cuda.current_stream()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for _ in range(a.steps):
+        job.step()
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_step = ev0.elapsed_time(ev1) / a.steps
+    recs = B.profile_records()
+    B.profile_enable(False)
+
+    by = {}
+    for label, ms in recs:
+        by.setdefault(label, []).append(ms)
+    kern = {k: {"launches_per_step": len(v) // a.steps, "avg_ms": float(np.mean(v)), "ms_per_step": float(np.sum(v)) / a.steps}
+            for k, v in by.items()}
+    attn = {k: v for k, v in kern.items() if k.startswith("attn")}
+    dom = max(attn, key=lambda k: attn[k]["ms_per_step"])
+    ach = kernel_flops(job, dom) / (kern[dom]["avg_ms"] * 1e-3) / 1e12
+    roofline = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
+    total_flops = job.flops_fwd + job.flops_bwd
+    value = total_flops / (ms_step * 1e-3) / 1e12
+    out = {
+        "metric": "causal attention TFLOP/s on packed varlen batch; % of bf16 MFMA peak",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": a.workload, "T": job.w["T"], "Hq": job.w["Hq"], "Hkv": job.w["Hkv"], "head_dim": job.w["d"],
+                   "n_sequences": len(job.lengths), "max_len": max(job.lengths), "n_long_chunked": job.n_long,
+                   "chunks": job.w["C"], "stages": "remap,fwd,chunk_partial,lse_merge,remap_inv,bwd,remap_inv"
+                   if job.w["remap"] else "fwd,bwd"},
+        "frac_of_mfma_peak": value / MFMA_BF16_PEAK_TFLOPS,
+        "roofline": roofline,
+        "kernels": kern,
+        "host_wall_ms_per_step": wall * 1e3 / a.steps,
+    }
+    fwd_ms = sum(kern[k]["ms_per_step"] for k in ("attn_fwd", "attn_fwd_partial", "lse_merge") if k in kern)
+    bwd_ms = sum(kern[k]["ms_per_step"] for k in ("attn_bwd_dq", "attn_bwd_dkdv") if k in kern)
+    out["fwd_tflops"] = job.flops_fwd / (fwd_ms * 1e-3) / 1e12 if fwd_ms else None
+    out["bwd_tflops"] = job.flops_bwd / (bwd_ms * 1e-3) / 1e12 if bwd_ms else None
+    if "remap" in kern:
+        gbps = job.remap_bytes / (kern["remap"]["ms_per_step"] * 1e-3) / 1e9
+        out["remap"] = {"GBps": gbps, "frac_of_hbm_peak": gbps / HBM_PEAK_GBPS, "bytes_per_step": job.remap_bytes}
+    if "lse_merge" in kern:
+        gbps = job.merge_bytes / (kern["lse_merge"]["ms_per_step"] * 1e-3) / 1e9
+        out["lse_merge"] = {"GBps": gbps, "frac_of_hbm_peak": gbps / HBM_PEAK_GBPS, "bytes_per_step": job.merge_bytes}
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(job)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

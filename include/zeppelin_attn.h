@@ -74,10 +74,12 @@ size_t zp_workspace_bytes(int which_fn, const zp_shape *sh, const int32_t *cu_se
  * The host builds a work list of (sequence, query block) tiles ordered by descending number of visible
  * key tiles -- the quadratic cost model |s|^2 of Alg. 2 applied per tile -- so that the heaviest tiles
  * start first and the light tail fills the gaps.
- * q,k,v: device bf16; o: device bf16 out; lse: device float32 [Hq][T] out; cu_seqlens_host: host [S+1]. */
+ * q,k,v: device bf16; o: device bf16 out; lse: device float32 [Hq][T] out; cu_seqlens_host: host [S+1].
+ * seq_skip_host: NULL, or host [S] flags; a flagged sequence is left out (its O / LSE rows are not written)
+ * so that the caller can compute it as chunk pairs instead (Sec. 3.2: ring sequences vs local sequences). */
 int varlen_attn_fwd(const void *q, const void *k, const void *v, int64_t q_stride, int64_t k_stride, int64_t v_stride,
-                    const int32_t *cu_seqlens_host, void *o, int64_t o_stride, float *lse, const zp_shape *sh, void *ws,
-                    size_t ws_bytes, void *stream);
+                    const int32_t *cu_seqlens_host, const uint8_t *seq_skip_host, void *o, int64_t o_stride, float *lse,
+                    const zp_shape *sh, void *ws, size_t ws_bytes, void *stream);
 
 /* Backward of varlen_attn_fwd (Sec. 5.4: the backward mirrors the forward with about twice the work).
  * Reads dO, Q, K, V and the forward's O and LSE; writes dQ [T][Hq][d], dK, dV [T][Hkv][d] (bf16). With
@@ -124,6 +126,15 @@ int remap_tokens(const void *src, void *dst, int64_t row_bytes, const int32_t *i
  * *n_merges and *rows_used (partial rows consumed). Negative on error. */
 int zp_chunk_pairs(int32_t tok0, int32_t L, int32_t C, int32_t rank, int32_t row0, zp_pair *pairs, int32_t max_pairs,
                    zp_merge *merges, int32_t max_merges, int32_t *n_merges, int64_t *rows_used);
+
+/* Measurement aid: per-kernel durations from hipEvents recorded on the launch stream.
+ * zp_profile_enable(1) clears the records and starts recording every kernel the library launches (one
+ * record per launch, in launch order); zp_profile_enable(0) stops and clears. zp_profile_get() waits for
+ * record i to finish and returns its kernel label (truncated to name_cap-1 chars) and duration in ms.
+ * Event creation is a host-side allocation: keep it off in production loops. */
+int zp_profile_enable(int on);
+int zp_profile_count(void);
+int zp_profile_get(int i, char *name, int name_cap, float *ms);
 
 const char *zp_strerror(int code);
 

@@ -56,7 +56,7 @@ def lib() -> ctypes.CDLL:
     L.zp_workspace_bytes.restype = sz
     L.zp_workspace_bytes.argtypes = [ctypes.c_int, ctypes.POINTER(ZpShape), vp, i64]
     L.varlen_attn_fwd.restype = ctypes.c_int
-    L.varlen_attn_fwd.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp, i64, vp, ctypes.POINTER(ZpShape), vp, sz, vp]
+    L.varlen_attn_fwd.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp, vp, i64, vp, ctypes.POINTER(ZpShape), vp, sz, vp]
     L.varlen_attn_bwd.restype = ctypes.c_int
     L.varlen_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, vp, vp, vp, vp, i64, i64,
                                   ctypes.POINTER(ZpShape), vp, sz, vp]
@@ -67,6 +67,11 @@ def lib() -> ctypes.CDLL:
     L.lse_merge.argtypes = [vp, vp, i64, ctypes.POINTER(ZpMerge), i32, vp, i64, vp, ctypes.POINTER(ZpShape), vp, sz, vp]
     L.remap_tokens.restype = ctypes.c_int
     L.remap_tokens.argtypes = [vp, vp, i64, vp, i64, i32, vp]
+    L.zp_profile_enable.restype = ctypes.c_int
+    L.zp_profile_enable.argtypes = [ctypes.c_int]
+    L.zp_profile_count.restype = ctypes.c_int
+    L.zp_profile_get.restype = ctypes.c_int
+    L.zp_profile_get.argtypes = [ctypes.c_int, ctypes.c_char_p, ctypes.c_int, ctypes.POINTER(ctypes.c_float)]
     L.zp_chunk_pairs.restype = ctypes.c_int
     L.zp_chunk_pairs.argtypes = [i32, i32, i32, i32, i32, ctypes.POINTER(ZpPair), i32, ctypes.POINTER(ZpMerge), i32,
                                  ctypes.POINTER(i32), ctypes.POINTER(i64)]
@@ -117,8 +122,9 @@ def make_shape(T, S, Hq, Hkv, d, scale=0.0) -> ZpShape:
     return ZpShape(int(T), int(S), int(Hq), int(Hkv), int(d), float(scale or 0.0))
 
 
-def varlen_attn_fwd(q, k, v, cu_seqlens, o=None, lse=None, scale=0.0, ws=None, stream=None):
-    """q [T,Hq,d], k/v [T,Hkv,d] bf16 device tensors -> (o [T,Hq,d] bf16, lse [Hq,T] f32)."""
+def varlen_attn_fwd(q, k, v, cu_seqlens, o=None, lse=None, scale=0.0, ws=None, stream=None, seq_skip=None):
+    """q [T,Hq,d], k/v [T,Hkv,d] bf16 device tensors -> (o [T,Hq,d] bf16, lse [Hq,T] f32).
+    seq_skip: optional per-sequence flags; flagged sequences are left for chunk_attn_partial + lse_merge."""
     cu = _cu_host(cu_seqlens)
     T, Hq, d = q.shape
     Hkv = k.shape[1]
@@ -130,8 +136,11 @@ def varlen_attn_fwd(q, k, v, cu_seqlens, o=None, lse=None, scale=0.0, ws=None, s
     need = workspace_bytes(FN_FWD, sh, cu)
     if ws is None:
         ws = workspace(need, q.device, "fwd")
+    skip = None if seq_skip is None else np.ascontiguousarray(seq_skip, dtype=np.uint8)
+    assert skip is None or len(skip) == len(cu) - 1
+    skp = None if skip is None else skip.ctypes.data_as(ctypes.c_void_p)
     _check(lib().varlen_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), _tok_stride(q), _tok_stride(k), _tok_stride(v),
-                                 cu.ctypes.data_as(ctypes.c_void_p), o.data_ptr(), _tok_stride(o), lse.data_ptr(),
+                                 cu.ctypes.data_as(ctypes.c_void_p), skp, o.data_ptr(), _tok_stride(o), lse.data_ptr(),
                                  ctypes.byref(sh), ws.data_ptr(), ws.numel(), _stream_ptr(stream)))
     return o, lse
 
@@ -238,3 +247,19 @@ def chunk_pairs(tok0: int, L: int, C: int, rank: int = -1, row0: int = 0):
     if n < 0:
         _check(n)
     return (ZpPair * n)(*pairs[:n]), (ZpMerge * nm.value)(*merges[:nm.value]), int(rows.value)
+
+
+def profile_enable(on: bool) -> None:
+    """Starts (clearing old records) or stops the library's per-kernel hipEvent timing."""
+    _check(lib().zp_profile_enable(1 if on else 0))
+
+
+def profile_records():
+    """[(kernel label, ms)] for every launch since profile_enable(True); waits for them to finish."""
+    out = []
+    buf = ctypes.create_string_buffer(64)
+    ms = ctypes.c_float(0)
+    for i in range(lib().zp_profile_count()):
+        _check(lib().zp_profile_get(i, buf, 64, ctypes.byref(ms)))
+        out.append((buf.value.decode(), float(ms.value)))
+    return out

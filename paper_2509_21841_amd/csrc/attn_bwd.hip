@@ -349,6 +349,9 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
 
 }  // namespace
 
+extern "C" void zp_prof_begin(const char *name, hipStream_t stream);
+extern "C" void zp_prof_end(hipStream_t stream);
+
 extern "C" int zp_attn_bwd_block_rows(int d, int which) { (void)d; (void)which; return 128; }
 
 extern "C" int zp_launch_attn_bwd(const zp_bwd_params *p, int d, hipStream_t stream) {
@@ -356,14 +359,18 @@ extern "C" int zp_launch_attn_bwd(const zp_bwd_params *p, int d, hipStream_t str
   const int kv_units = p->n_kv_tiles * p->Hkv;
   if (dq_units > 0) {
     const int grid = ((dq_units + 7) / 8) * 8 * p->grp;
+    zp_prof_begin("attn_bwd_dq", stream);
     if (d == 128) hipLaunchKernelGGL((attn_bwd_dq_kernel<128>), dim3(grid), dim3(BWD_NT), 4 * 64 * 128 * 2, stream, *p);
     else hipLaunchKernelGGL((attn_bwd_dq_kernel<64>), dim3(grid), dim3(BWD_NT), 4 * 64 * 64 * 2, stream, *p);
+    zp_prof_end(stream);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
   }
   if (kv_units > 0) {
+    zp_prof_begin("attn_bwd_dkdv", stream);
     if (d == 128) hipLaunchKernelGGL((attn_bwd_dkdv_kernel<128>), dim3(kv_units), dim3(BWD_NT), 4 * 64 * 128 * 2 + 1024, stream, *p);
     else hipLaunchKernelGGL((attn_bwd_dkdv_kernel<64>), dim3(kv_units), dim3(BWD_NT), 4 * 64 * 64 * 2 + 1024, stream, *p);
+    zp_prof_end(stream);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
   }

@@ -212,6 +212,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
 }  // namespace
 
+extern "C" void zp_prof_begin(const char *name, hipStream_t stream);
+extern "C" void zp_prof_end(hipStream_t stream);
+
 // Host-side launcher used by the C ABI. Returns a hipError_t as int.
 extern "C" int zp_launch_attn_fwd(const zp_attn_params *p, int d, int partial, int block_rows, hipStream_t stream) {
   const int units = p->n_tiles * p->Hkv;
@@ -221,7 +224,9 @@ extern "C" int zp_launch_attn_fwd(const zp_attn_params *p, int d, int partial, i
 #define ZP_FWD_LAUNCH(D, NW, PART)                                                                      \
   do {                                                                                                  \
     size_t lds = 4 * (size_t)FwdCfg<D, NW>::TILEB;                                                      \
+    zp_prof_begin(PART ? "attn_fwd_partial" : "attn_fwd", stream);                                      \
     hipLaunchKernelGGL((attn_fwd_kernel<D, NW, PART>), dim3(grid), dim3(NW * 64), lds, stream, *p);     \
+    zp_prof_end(stream);                                                                                \
   } while (0)
   if (d == 128) {
     if (partial) ZP_FWD_LAUNCH(128, 4, true); else ZP_FWD_LAUNCH(128, 4, false);

@@ -64,14 +64,19 @@ __global__ __launch_bounds__(MERGE_NT) void lse_merge_kernel(const float *__rest
 }
 }  // namespace
 
+extern "C" void zp_prof_begin(const char *name, hipStream_t stream);
+extern "C" void zp_prof_end(hipStream_t stream);
+
 extern "C" int zp_merge_rows_per_item(void) { return MERGE_ROWS; }
 
 extern "C" int zp_launch_lse_merge(const float *o_part, const float *lse_part, int64_t part_rows, const void *merges_dev,
                                    const void *items_dev, int n_items, int Hq, int d, void *o, int64_t o_stride,
                                    float *lse, int64_t T, hipStream_t stream) {
   if (n_items == 0) return 0;
+  zp_prof_begin("lse_merge", stream);
   hipLaunchKernelGGL(lse_merge_kernel, dim3(n_items), dim3(MERGE_NT), 0, stream, o_part, lse_part, part_rows,
                      (const zp_merge_dev *)merges_dev, (const zp_merge_item *)items_dev, Hq, d, (__bf16 *)o, o_stride,
                      lse, T);
+  zp_prof_end(stream);
   return (int)hipGetLastError();
 }

@@ -43,6 +43,9 @@ __global__ __launch_bounds__(REMAP_NT) void remap_kernel(const u32x4 *__restrict
 
 }  // namespace
 
+extern "C" void zp_prof_begin(const char *name, hipStream_t stream);
+extern "C" void zp_prof_end(hipStream_t stream);
+
 extern "C" int zp_launch_remap(const void *src, void *dst, int64_t row_bytes, const int32_t *idx, int64_t n_rows,
                                int mode, hipStream_t stream) {
   if (n_rows == 0) return 0;
@@ -55,6 +58,7 @@ extern "C" int zp_launch_remap(const void *src, void *dst, int64_t row_bytes, co
   const int64_t grid = (n_rows + rpb - 1) / rpb;
   const u32x4 *s = (const u32x4 *)src;
   u32x4 *d = (u32x4 *)dst;
+  zp_prof_begin("remap", stream);
   if (mode == 0) {
     if (shift >= 0) hipLaunchKernelGGL((remap_kernel<false, true>), dim3((unsigned)grid), dim3(REMAP_NT), 0, stream, s, d, idx, n_rows, cpr, shift, rpb);
     else hipLaunchKernelGGL((remap_kernel<false, false>), dim3((unsigned)grid), dim3(REMAP_NT), 0, stream, s, d, idx, n_rows, cpr, shift, rpb);
@@ -62,5 +66,6 @@ extern "C" int zp_launch_remap(const void *src, void *dst, int64_t row_bytes, co
     if (shift >= 0) hipLaunchKernelGGL((remap_kernel<true, true>), dim3((unsigned)grid), dim3(REMAP_NT), 0, stream, s, d, idx, n_rows, cpr, shift, rpb);
     else hipLaunchKernelGGL((remap_kernel<true, false>), dim3((unsigned)grid), dim3(REMAP_NT), 0, stream, s, d, idx, n_rows, cpr, shift, rpb);
   }
+  zp_prof_end(stream);
   return (int)hipGetLastError();
 }

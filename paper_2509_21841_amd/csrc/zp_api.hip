@@ -109,6 +109,17 @@ void pool_release_unused(int slot) {
   g_pool[slot].in_flight = false;
 }
 
+// ---- per-kernel timing (measurement aid) -----------------------------------------------------------
+// When enabled, every kernel launch is bracketed by a pair of hipEvents on the launch stream; the bench reads
+// the elapsed times after it has synchronised. Off by default: no events are created or recorded.
+struct ProfRec {
+  const char *name;
+  hipEvent_t a, b;
+};
+std::mutex g_prof_mu;
+bool g_prof_on = false;
+std::vector<ProfRec> g_prof;
+
 // ---- checks --------------------------------------------------------------------------------------
 int check_shape(const zp_shape *sh) {
   if (!sh) return ZP_EINVAL;
@@ -156,8 +167,9 @@ int64_t count_blocks(const int32_t *cu, int S, int bm) {
   for (int s = 0; s < S; s++) n += ((int64_t)cu[s + 1] - cu[s] + bm - 1) / bm;
   return n;
 }
-void plan_whole(const int32_t *cu, int S, int bm, std::vector<CostTile> &out) {
+void plan_whole(const int32_t *cu, int S, int bm, std::vector<CostTile> &out, const uint8_t *skip = nullptr) {
   for (int s = 0; s < S; s++) {
+    if (skip && skip[s]) continue;
     const int32_t L = cu[s + 1] - cu[s];
     for (int32_t r0 = 0; r0 < L; r0 += bm) {
       CostTile c;
@@ -197,6 +209,42 @@ int upload_tiles(const std::vector<CostTile> &tiles, void *ws, hipStream_t strea
 }  // namespace
 
 extern "C" {
+
+void zp_prof_begin(const char *name, hipStream_t stream) {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  if (!g_prof_on) return;
+  ProfRec r{name, nullptr, nullptr};
+  if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return;
+  (void)hipEventRecord(r.a, stream);
+  g_prof.push_back(r);
+}
+void zp_prof_end(hipStream_t stream) {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  if (!g_prof_on || g_prof.empty()) return;
+  (void)hipEventRecord(g_prof.back().b, stream);
+}
+int zp_profile_enable(int on) {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  for (auto &r : g_prof) {
+    (void)hipEventDestroy(r.a);
+    (void)hipEventDestroy(r.b);
+  }
+  g_prof.clear();
+  g_prof_on = on != 0;
+  return ZP_OK;
+}
+int zp_profile_count(void) {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  return (int)g_prof.size();
+}
+int zp_profile_get(int i, char *name, int name_cap, float *ms) {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  if (i < 0 || i >= (int)g_prof.size() || !name || name_cap < 1 || !ms) return ZP_EINVAL;
+  ZP_HIP(hipEventSynchronize(g_prof[i].b), "hipEventSynchronize");
+  ZP_HIP(hipEventElapsedTime(ms, g_prof[i].a, g_prof[i].b), "hipEventElapsedTime");
+  std::snprintf(name, (size_t)name_cap, "%s", g_prof[i].name);
+  return ZP_OK;
+}
 
 const char *zp_strerror(int code) {
   switch (code) {
@@ -239,8 +287,8 @@ size_t zp_workspace_bytes(int which_fn, const zp_shape *sh, const int32_t *cu, i
 }
 
 int varlen_attn_fwd(const void *q, const void *k, const void *v, int64_t q_stride, int64_t k_stride, int64_t v_stride,
-                    const int32_t *cu, void *o, int64_t o_stride, float *lse, const zp_shape *sh, void *ws,
-                    size_t ws_bytes, void *stream) {
+                    const int32_t *cu, const uint8_t *seq_skip, void *o, int64_t o_stride, float *lse,
+                    const zp_shape *sh, void *ws, size_t ws_bytes, void *stream) {
   int rc = check_shape(sh);
   if (rc) return rc;
   if ((rc = check_cu(cu, sh))) return rc;
@@ -253,7 +301,8 @@ int varlen_attn_fwd(const void *q, const void *k, const void *v, int64_t q_strid
   const int bm = zp_attn_fwd_block_rows(sh->d);
   std::vector<CostTile> tiles;
   tiles.reserve((size_t)count_blocks(cu, sh->S, bm));
-  plan_whole(cu, sh->S, bm, tiles);
+  plan_whole(cu, sh->S, bm, tiles, seq_skip);
+  if (tiles.empty()) return ZP_OK;
   if ((rc = check_ws(ws, ws_bytes, align256(tiles.size() * sizeof(zp_tile))))) return rc;
   if ((rc = upload_tiles(tiles, ws, (hipStream_t)stream))) return rc;
   zp_attn_params p{};

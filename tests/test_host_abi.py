@@ -39,7 +39,7 @@ def _fwd_rc(sh, cu, q=1 << 12, k=1 << 12, v=1 << 12, o=1 << 12, lse=1 << 12, qs=
     L = B.lib()
     cu = np.ascontiguousarray(cu, np.int32)
     qs = sh.Hq * sh.d if qs is None else qs
-    return L.varlen_attn_fwd(q, k, v, qs, sh.Hkv * sh.d, sh.Hkv * sh.d, cu.ctypes.data_as(ctypes.c_void_p), o,
+    return L.varlen_attn_fwd(q, k, v, qs, sh.Hkv * sh.d, sh.Hkv * sh.d, cu.ctypes.data_as(ctypes.c_void_p), None, o,
                              sh.Hq * sh.d, lse, ctypes.byref(sh), ws, wsb, None)
 
 
