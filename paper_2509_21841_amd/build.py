@@ -12,7 +12,9 @@ LIB = os.path.join(HERE, "libzeppelin_attn.so")
 SOURCES = ["zp_api.hip", "attn_fwd.hip", "attn_bwd.hip", "lse_merge.hip", "remap.hip"]
 # packed-fp32 VALU forms are switched off on purpose for this target
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
-         "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
+         "-packed-fp32-ops", "-Wno-unused-command-line-argument",
+         # keep MFMA results in ordinary VGPRs where possible: avoids accumulator-register copy storms
+         "-mllvm", "-amdgpu-mfma-vgpr-form=1"]
 
 
 def _hipcc() -> str:

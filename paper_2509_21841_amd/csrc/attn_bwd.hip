@@ -13,6 +13,7 @@ struct zp_bwd_params {
   int64_t q_stride, k_stride, v_stride, o_stride, do_stride;
   const float *lse;   // [Hq][T]
   float *dvec;        // [Hq][T] scratch: D_i = dO_i . O_i
+  float *lse2;        // [Hq][T] scratch: LSE_i * log2(e)
   const zp_tile *dq_tiles;
   const zp_tile *kv_tiles;
   int32_t n_dq_tiles, n_kv_tiles, Hq, Hkv, grp, T;
@@ -113,7 +114,10 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
   float lse2 = 0.f;
   if (row_ok) {
     lse2 = p.lse[(int64_t)h * p.T + tok] * LOG2E;
-    if (hi == 0) p.dvec[(int64_t)h * p.T + tok] = Dq;
+    if (hi == 0) {
+      p.dvec[(int64_t)h * p.T + tok] = Dq;
+      p.lse2[(int64_t)h * p.T + tok] = lse2;
+    }
   }
 
   const __bf16 *kbase = p.k + (int64_t)t.k_tok0 * p.k_stride + (int64_t)g * D;
@@ -198,14 +202,111 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
 // ------------------------------------------------------------------------------------------- dK, dV
 // Tile fields: k_tok0/k_len/k_pos0 = this block of key rows; q_tok0/q_rows/q_pos0 = the query rows of the
 // same sequence from the first one that can see the block's first key to the end of the sequence.
+//
+// One wave per SIMD (the 128 accumulator registers of dK^T and dV^T plus the K/V operands leave no room for
+// two), so latency is hidden inside the wave: per 64-query tile the two 32-query blocks are software
+// pipelined -- LDS operands are fetched a phase ahead, the exp/scale arithmetic of one block is interleaved
+// with the MFMAs of the other.
+#define ZP_SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
+#define ZP_SG_MFMA 0x008
+#define ZP_SG_VALU 0x002
+#define ZP_SG_TRANS 0x400
+#define ZP_SG_DSREAD 0x100
+
+template <int D, bool MASK>
+__device__ __forceinline__ void dkdv_pds(const f32x16 &s, const f32x16 &dp, const float *Lb, const float *Db, int qb,
+                                         int hi, int qpos0, int kpos, int qpos_end, float c_log2, bf16x8 (&pb)[2],
+                                         bf16x8 (&dsb)[2]) {
+#pragma unroll
+  for (int b = 0; b < 4; b++) {
+    const f32x4 l4 = *(const ZP_LDS f32x4 *)((const ZP_LDS char *)Lb + (qb * 32 + 8 * b + 4 * hi) * 4);
+    const f32x4 d4 = *(const ZP_LDS f32x4 *)((const ZP_LDS char *)Db + (qb * 32 + 8 * b + 4 * hi) * 4);
+#pragma unroll
+    for (int c = 0; c < 4; c++) {
+      const int r = 4 * b + c;
+      float sv = s[r];
+      if (MASK) {
+        const int qpos = qpos0 + qb * 32 + 8 * b + 4 * hi + c;
+        if (qpos < kpos || qpos >= qpos_end) sv = -INFINITY;
+      }
+      const float pv = zp_exp2(__builtin_fmaf(sv, c_log2, -l4[c]));
+      pb[r >> 3][r & 7] = (__bf16)pv;
+      dsb[r >> 3][r & 7] = (__bf16)(pv * (dp[r] - d4[c]));
+    }
+  }
+}
+
+// One 64-query tile = two 32-query blocks, processed in phases with the LDS operands of the next phase
+// requested before the arithmetic of the current one:
+//   rows(0) | S,dP(0) | tr(0) requested, P,dS(0) | rows(1) requested, dV,dK(0) | S,dP(1) | tr(1), P,dS(1) | dV,dK(1)
+template <int D, bool MASK>
+__device__ __forceinline__ void dkdv_tile(const char *Qb, const char *Ob, const float *Lb, const float *Db,
+                                          const bf16x8 (&kreg)[D / 16], const bf16x8 (&vreg)[D / 16],
+                                          f32x16 (&dk_acc)[D / 32], f32x16 (&dv_acc)[D / 32], int qpos0, int kpos,
+                                          int qpos_end, float c_log2, int kl, int hi, int trow, int tcol) {
+  constexpr int KK = D / 16, DB = D / 32;
+  bf16x8 aq[KK], ao[KK];
+  bf16x8 to[2][DB], tq[2][DB];
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+  auto load_rows = [&](int qb) {
+#pragma unroll
+    for (int kk = 0; kk < KK; kk++) aq[kk] = zp_lds_read16(Qb, zp_swz<D>(qb * 32 + kl, 2 * kk + hi));
+#pragma unroll
+    for (int kk = 0; kk < KK; kk++) ao[kk] = zp_lds_read16(Ob, zp_swz<D>(qb * 32 + kl, 2 * kk + hi));
+  };
+  auto load_tr = [&](int qb) {
+#pragma unroll
+    for (int m = 0; m < 2; m++)
+#pragma unroll
+      for (int db = 0; db < DB; db++) {
+        to[m][db] = zp_cat(zp_lds_read_tr(Ob, zp_swz_col<D>(qb * 32 + m * 16 + trow, db * 32 + tcol)),
+                           zp_lds_read_tr(Ob, zp_swz_col<D>(qb * 32 + m * 16 + 8 + trow, db * 32 + tcol)));
+        tq[m][db] = zp_cat(zp_lds_read_tr(Qb, zp_swz_col<D>(qb * 32 + m * 16 + trow, db * 32 + tcol)),
+                           zp_lds_read_tr(Qb, zp_swz_col<D>(qb * 32 + m * 16 + 8 + trow, db * 32 + tcol)));
+      }
+  };
+
+  load_rows(0);
+#pragma unroll
+  for (int qb = 0; qb < 2; qb++) {
+    f32x16 s, dp;
+    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[0], kreg[0], zero, 0, 0, 0);
+    dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ao[0], vreg[0], zero, 0, 0, 0);
+#pragma unroll
+    for (int kk = 1; kk < KK; kk++) {
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[kk], kreg[kk], s, 0, 0, 0);
+      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ao[kk], vreg[kk], dp, 0, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    load_tr(qb);
+    __builtin_amdgcn_sched_barrier(0);
+    bf16x8 pb[2], dsb[2];
+    dkdv_pds<D, MASK>(s, dp, Lb, Db, qb, hi, qpos0, kpos, qpos_end, c_log2, pb, dsb);
+    __builtin_amdgcn_sched_barrier(0);
+    if (qb == 0) load_rows(1);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int m = 0; m < 2; m++)
+#pragma unroll
+      for (int db = 0; db < DB; db++) {
+        dv_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(to[m][db], pb[m], dv_acc[db], 0, 0, 0);
+        dk_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq[m][db], dsb[m], dk_acc[db], 0, 0, 0);
+      }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
 template <int D>
 __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void attn_bwd_dkdv_kernel(zp_bwd_params p) {
   constexpr int TILEB = 64 * D * 2;
+  constexpr int NBUF = 4;                       // tiles are fetched three iterations ahead
+  constexpr int LOADS = 2 * (TILEB / 4096) + 2; // async loads one wave issues per staged tile
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  char *Qs = smem;                              // [2][64][D]
-  char *Os = smem + 2 * TILEB;                  // [2][64][D]  (dO)
-  float *Ls = (float *)(smem + 4 * TILEB);      // [2][64] LSE * log2(e)
-  float *Ds = Ls + 128;                         // [2][64] D
+  char *Qs = smem;                              // [NBUF][64][D]
+  char *Os = smem + NBUF * TILEB;               // [NBUF][64][D]  (dO)
+  float *Ls = (float *)(smem + 2 * NBUF * TILEB);  // [NBUF][64] LSE * log2(e)
+  float *Ds = Ls + NBUF * 64;                   // [NBUF][64] D
 
   const int unit = blockIdx.x;
   if (unit >= p.n_kv_tiles * p.Hkv) return;
@@ -235,6 +336,10 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
     }
   }
 
+  // the register operands must have arrived before any asynchronous tile copy is issued: a later wait for
+  // them would also drain those copies
+  zp_wait_async();
+
   f32x16 dk_acc[D / 32], dv_acc[D / 32];
 #pragma unroll
   for (int i = 0; i < D / 32; i++)
@@ -244,101 +349,53 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
 
   const int n_qt = (t.q_rows + 63) / 64;
   const int n_it = n_qt * p.grp;  // iterations: heads of the group outermost, query tiles innermost
-  TileStage<D> qst, ost;
-  float lpre = 0.f, dpre = 0.f;
 
-  auto load_it = [&](int it) {
+  auto stage = [&](int it, int buf) {
     const int hh = it / n_qt, i0 = (it - hh * n_qt) * 64;
     const int h = g * p.grp + hh;
-    const __bf16 *qb = p.q + (int64_t)t.q_tok0 * p.q_stride + (int64_t)h * D;
-    const __bf16 *ob = p.dout + (int64_t)t.q_tok0 * p.do_stride + (int64_t)h * D;
-    qst.load(qb, p.q_stride, i0, t.q_rows, tid);
-    ost.load(ob, p.do_stride, i0, t.q_rows, tid);
-    if (tid < 64) {
-      const bool ok = i0 + tid < t.q_rows;
-      const int64_t idx = (int64_t)h * p.T + t.q_tok0 + i0 + tid;
-      lpre = ok ? p.lse[idx] * LOG2E : 0.f;
-      dpre = ok ? p.dvec[idx] : 0.f;
-    }
-  };
-  auto store_it = [&](int buf) {
-    qst.store(Qs + buf * TILEB, tid);
-    ost.store(Os + buf * TILEB, tid);
-    if (tid < 64) {
-      Ls[buf * 64 + tid] = lpre;
-      Ds[buf * 64 + tid] = dpre;
-    }
+    zp_stage_async<D>(Qs + buf * TILEB, p.q + (int64_t)t.q_tok0 * p.q_stride + (int64_t)h * D, p.q_stride, i0, t.q_rows, tid);
+    zp_stage_async<D>(Os + buf * TILEB, p.dout + (int64_t)t.q_tok0 * p.do_stride + (int64_t)h * D, p.do_stride, i0, t.q_rows, tid);
+    const int64_t base = (int64_t)h * p.T + t.q_tok0;
+    zp_stage_async_f32x64(Ls + buf * 64, p.lse2 + base, i0, t.q_rows - 1, lane);
+    zp_stage_async_f32x64(Ds + buf * 64, p.dvec + base, i0, t.q_rows - 1, lane);
   };
 
-  if (n_it > 0) {
-    load_it(0);
-    store_it(0);
-  }
+  // prologue: up to NBUF-1 tiles in flight; tile 0 must have landed before the first iteration
+  if (n_it > 0) stage(0, 0);
+  if (n_it > 1) stage(1, 1);
+  if (n_it > 2) stage(2, 2);
+  if (n_it > 2) zp_wait_async_upto<2 * LOADS>();
+  else if (n_it > 1) zp_wait_async_upto<LOADS>();
+  else zp_wait_async();
   __syncthreads();
 
   const int g16 = lane >> 4, i16 = lane & 15;
   const int trow = 4 * (g16 >> 1) + (i16 >> 2);
   const int tcol = 16 * (g16 & 1) + 4 * (i16 & 3);
   const int kpos_w_min = t.k_pos0 + w * 32, kpos_w_max = t.k_pos0 + w * 32 + 31;
+  const int qpos_end = t.q_pos0 + t.q_rows;
 
+  int buf = 0;
   for (int it = 0; it < n_it; it++) {
-    const int buf = it & 1;
     const int hh = it / n_qt, i0 = (it - hh * n_qt) * 64;
-    if (it + 1 < n_it) load_it(it + 1);
+    const int ahead = n_it - 1 - it;  // tiles after this one
+    if (ahead >= NBUF - 1) stage(it + NBUF - 1, (buf + NBUF - 1) & (NBUF - 1));
 
     const int qpos0 = t.q_pos0 + i0;  // position of the tile's first query
     if (qpos0 + 63 >= kpos_w_min) {   // otherwise every query of the tile precedes every key of this wave
       const char *Qb = Qs + buf * TILEB;
       const char *Ob = Os + buf * TILEB;
-      const bool need_mask = qpos0 < kpos_w_max;
-#pragma unroll
-      for (int qb = 0; qb < 2; qb++) {
-        f32x16 s, dp;
-#pragma unroll
-        for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = 0.f; }
-#pragma unroll
-        for (int kk = 0; kk < D / 16; kk++) {
-          bf16x8 a = zp_lds_read16(Qb, zp_swz<D>(qb * 32 + kl, 2 * kk + hi));
-          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kreg[kk], s, 0, 0, 0);
-        }
-#pragma unroll
-        for (int kk = 0; kk < D / 16; kk++) {
-          bf16x8 a = zp_lds_read16(Ob, zp_swz<D>(qb * 32 + kl, 2 * kk + hi));
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, vreg[kk], dp, 0, 0, 0);
-        }
-        bf16x8 pb[2], dsb[2];
-#pragma unroll
-        for (int b = 0; b < 4; b++) {
-          const f32x4 l4 = *(const ZP_LDS f32x4 *)((const ZP_LDS char *)(Ls + buf * 64) + (qb * 32 + 8 * b + 4 * hi) * 4);
-          const f32x4 d4 = *(const ZP_LDS f32x4 *)((const ZP_LDS char *)(Ds + buf * 64) + (qb * 32 + 8 * b + 4 * hi) * 4);
-#pragma unroll
-          for (int c = 0; c < 4; c++) {
-            const int r = 4 * b + c;
-            float sv = s[r];
-            if (need_mask) {
-              const int qpos = qpos0 + qb * 32 + 8 * b + 4 * hi + c;
-              if (qpos < kpos) sv = -INFINITY;
-            }
-            const float pv = zp_exp2(__builtin_fmaf(sv, c_log2, -l4[c]));
-            pb[r >> 3][r & 7] = (__bf16)pv;
-            dsb[r >> 3][r & 7] = (__bf16)(pv * (dp[r] - d4[c]));
-          }
-        }
-#pragma unroll
-        for (int m = 0; m < 2; m++)
-#pragma unroll
-          for (int db = 0; db < D / 32; db++) {
-            bf16x4 lo = zp_lds_read_tr(Ob, zp_swz_col<D>(qb * 32 + m * 16 + trow, db * 32 + tcol));
-            bf16x4 hi4 = zp_lds_read_tr(Ob, zp_swz_col<D>(qb * 32 + m * 16 + 8 + trow, db * 32 + tcol));
-            dv_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zp_cat(lo, hi4), pb[m], dv_acc[db], 0, 0, 0);
-            bf16x4 lo2 = zp_lds_read_tr(Qb, zp_swz_col<D>(qb * 32 + m * 16 + trow, db * 32 + tcol));
-            bf16x4 hi2 = zp_lds_read_tr(Qb, zp_swz_col<D>(qb * 32 + m * 16 + 8 + trow, db * 32 + tcol));
-            dk_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zp_cat(lo2, hi2), dsb[m], dk_acc[db], 0, 0, 0);
-          }
-      }
+      if (qpos0 < kpos_w_max || qpos0 + 64 > qpos_end)
+        dkdv_tile<D, true>(Qb, Ob, Ls + buf * 64, Ds + buf * 64, kreg, vreg, dk_acc, dv_acc, qpos0, kpos, qpos_end, c_log2, kl, hi, trow, tcol);
+      else
+        dkdv_tile<D, false>(Qb, Ob, Ls + buf * 64, Ds + buf * 64, kreg, vreg, dk_acc, dv_acc, qpos0, kpos, qpos_end, c_log2, kl, hi, trow, tcol);
     }
-    if (it + 1 < n_it) store_it(buf ^ 1);
+    // the next tile must have landed; the ones behind it may stay in flight
+    if (ahead >= NBUF - 1) zp_wait_async_upto<(NBUF - 2) * LOADS>();
+    else if (ahead == 2) zp_wait_async_upto<LOADS>();
+    else zp_wait_async();
     __syncthreads();
+    buf = (buf + 1) & (NBUF - 1);
   }
 
   if (key_ok) {
@@ -368,8 +425,8 @@ extern "C" int zp_launch_attn_bwd(const zp_bwd_params *p, int d, hipStream_t str
   }
   if (kv_units > 0) {
     zp_prof_begin("attn_bwd_dkdv", stream);
-    if (d == 128) hipLaunchKernelGGL((attn_bwd_dkdv_kernel<128>), dim3(kv_units), dim3(BWD_NT), 4 * 64 * 128 * 2 + 1024, stream, *p);
-    else hipLaunchKernelGGL((attn_bwd_dkdv_kernel<64>), dim3(kv_units), dim3(BWD_NT), 4 * 64 * 64 * 2 + 1024, stream, *p);
+    if (d == 128) hipLaunchKernelGGL((attn_bwd_dkdv_kernel<128>), dim3(kv_units), dim3(BWD_NT), 8 * 64 * 128 * 2 + 2048, stream, *p);
+    else hipLaunchKernelGGL((attn_bwd_dkdv_kernel<64>), dim3(kv_units), dim3(BWD_NT), 8 * 64 * 64 * 2 + 2048, stream, *p);
     zp_prof_end(stream);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;

@@ -27,6 +27,7 @@ struct zp_bwd_params {
   int64_t q_stride, k_stride, v_stride, o_stride, do_stride;
   const float *lse;
   float *dvec;
+  float *lse2;
   const zp_tile *dq_tiles;
   const zp_tile *kv_tiles;
   int32_t n_dq_tiles, n_kv_tiles, Hq, Hkv, grp, T;
@@ -280,7 +281,7 @@ size_t zp_workspace_bytes(int which_fn, const zp_shape *sh, const int32_t *cu, i
       if (check_cu(cu, sh) != ZP_OK) return 0;
       const size_t tiles = (size_t)count_blocks(cu, sh->S, zp_attn_bwd_block_rows(sh->d, 0)) +
                            (size_t)count_blocks(cu, sh->S, zp_attn_bwd_block_rows(sh->d, 1));
-      return align256(tiles * sizeof(zp_tile)) + align256((size_t)sh->Hq * (size_t)sh->T * sizeof(float)) + 512;
+      return align256(tiles * sizeof(zp_tile)) + 2 * align256((size_t)sh->Hq * (size_t)sh->T * sizeof(float)) + 512;
     }
     default: return 0;
   }
@@ -489,7 +490,14 @@ extern "C" int varlen_attn_bwd(const void *dout, const void *q, const void *k, c
   qt.reserve((size_t)count_blocks(cu, sh->S, bmq));
   plan_whole(cu, sh->S, bmq, qt);
   kt.reserve((size_t)count_blocks(cu, sh->S, bnk));
-  for (int s = 0; s < sh->S; s++) {
+  // Key-block tiles go sequence by sequence, longest sequence first, blocks in position order (descending
+  // cost inside the sequence): workgroups that run side by side then walk the same Q/dO rows a few tiles
+  // apart and find them in L2, and the cheap blocks of the short sequences still come last.
+  std::vector<int> seq_order(sh->S);
+  for (int s = 0; s < sh->S; s++) seq_order[s] = s;
+  std::stable_sort(seq_order.begin(), seq_order.end(),
+                   [&](int a, int b) { return cu[a + 1] - cu[a] > cu[b + 1] - cu[b]; });
+  for (int s : seq_order) {
     const int32_t L = cu[s + 1] - cu[s];
     for (int32_t j0 = 0; j0 < L; j0 += bnk) {
       CostTile c;
@@ -505,10 +513,9 @@ extern "C" int varlen_attn_bwd(const void *dout, const void *q, const void *k, c
       kt.push_back(c);
     }
   }
-  sort_by_cost(kt);
   const size_t tile_bytes = align256((qt.size() + kt.size()) * sizeof(zp_tile));
   const size_t dvec_bytes = align256((size_t)sh->Hq * (size_t)sh->T * sizeof(float));
-  if ((rc = check_ws(ws, ws_bytes, tile_bytes + dvec_bytes))) return rc;
+  if ((rc = check_ws(ws, ws_bytes, tile_bytes + 2 * dvec_bytes))) return rc;
   std::vector<CostTile> all(qt);
   all.insert(all.end(), kt.begin(), kt.end());
   if ((rc = upload_tiles(all, ws, (hipStream_t)stream))) return rc;
@@ -518,6 +525,7 @@ extern "C" int varlen_attn_bwd(const void *dout, const void *q, const void *k, c
   p.q_stride = q_stride; p.k_stride = k_stride; p.v_stride = v_stride; p.o_stride = o_stride; p.do_stride = do_stride;
   p.lse = lse;
   p.dvec = (float *)((char *)ws + tile_bytes);
+  p.lse2 = (float *)((char *)ws + tile_bytes + dvec_bytes);
   p.dq_tiles = (const zp_tile *)ws;
   p.kv_tiles = (const zp_tile *)ws + qt.size();
   p.n_dq_tiles = (int32_t)qt.size(); p.n_kv_tiles = (int32_t)kt.size();

@@ -113,3 +113,60 @@ template <int D>
 __device__ __forceinline__ int zp_swz_col(int row, int col) {
   return zp_swz<D>(row, col >> 3) + ((col & 7) << 1);
 }
+
+// ---- asynchronous global -> LDS copies -------------------------------------------------------------
+// The direct-to-LDS loads are issued from inline assembly so that they stay truly asynchronous: the
+// compiler does not track them, inserts no waits for them, and its workgroup barriers do not drain them.
+// Ordering is explicit: zp_wait_async*() before the barrier that publishes a staged tile. Each lane's bytes
+// land at (wave-uniform LDS base in M0) + lane * size.
+__device__ __forceinline__ unsigned zp_lds_addr(const void *p) {
+  return (unsigned)(unsigned long long)(ZP_LDS const char *)p;
+}
+__device__ __forceinline__ void zp_dma16(const void *g, unsigned lds_base_uniform) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off\n" ::"v"(g), "s"(lds_base_uniform) : "memory");
+}
+__device__ __forceinline__ void zp_dma4(const void *g, unsigned lds_base_uniform) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off\n" ::"v"(g), "s"(lds_base_uniform) : "memory");
+}
+
+// Staging of a [64][D] bf16 tile in the zp_swz layout without passing through registers: the swizzle is
+// applied by choosing WHICH global chunk a lane fetches. Rows past rows_total are clamped to the last valid
+// row (the callers mask them). 256 threads; every wave issues 64*D*2/4096 loads.
+template <int D>
+__device__ __forceinline__ void zp_stage_async(char *lds_tile, const __bf16 *gbase, int64_t stride, int row0,
+                                               int rows_total, int tid) {
+  const int lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  constexpr int PER_WAVE = 64 * D * 2 / 1024 / 4;  // 1 KiB wave-loads per wave
+  const unsigned lds0 = __builtin_amdgcn_readfirstlane(zp_lds_addr(lds_tile));
+#pragma unroll
+  for (int n = 0; n < PER_WAVE; n++) {
+    const int blk = w * PER_WAVE + n;  // 1 KiB block of the tile
+    int r, c;
+    if (D == 128) {
+      r = blk * 4 + (lane >> 4);
+      c = (lane & 15) ^ (((r & 3) << 2) | ((r >> 2) & 3));
+    } else {
+      r = blk * 8 + (lane >> 3);
+      c = (lane & 7) ^ (((r & 1) << 2) | ((r >> 1) & 3));
+    }
+    int gr = row0 + r;
+    if (gr > rows_total - 1) gr = rows_total - 1;
+    zp_dma16(gbase + (int64_t)gr * stride + c * 8, lds0 + blk * 1024);
+  }
+}
+// Copy of 64 consecutive floats (one per lane), issued by every wave of the workgroup to the same
+// destination so that all waves have the same number of loads in flight.
+__device__ __forceinline__ void zp_stage_async_f32x64(float *lds_dst, const float *gsrc, int first, int last_valid,
+                                                      int lane) {
+  int i = first + lane;
+  if (i > last_valid) i = last_valid;
+  zp_dma4(gsrc + i, __builtin_amdgcn_readfirstlane(zp_lds_addr(lds_dst)));
+}
+// wait for every outstanding vector-memory operation of this wave (vmcnt = 0), nothing else
+__device__ __forceinline__ void zp_wait_async() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+// wait until at most N vector-memory operations of this wave are outstanding (N compile-time, <= 63)
+template <int N>
+__device__ __forceinline__ void zp_wait_async_upto() {
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
