@@ -12,8 +12,8 @@ struct zp_bwd_params {
   const __bf16 *q, *k, *v, *o, *dout;
   int64_t q_stride, k_stride, v_stride, o_stride, do_stride;
   const float *lse;   // [Hq][T]
-  float *dvec;        // [Hq][T] scratch: D_i = dO_i . O_i
-  float *lse2;        // [Hq][T] scratch: LSE_i * log2(e)
+  float *dvec;        // [Hq][T] scratch: -D_i = -(dO_i . O_i)
+  float *lse2;        // [Hq][T] scratch: -LSE_i / scale
   const zp_tile *dq_tiles;
   const zp_tile *kv_tiles;
   int32_t n_dq_tiles, n_kv_tiles, Hq, Hkv, grp, T;
@@ -115,8 +115,9 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
   if (row_ok) {
     lse2 = p.lse[(int64_t)h * p.T + tok] * LOG2E;
     if (hi == 0) {
-      p.dvec[(int64_t)h * p.T + tok] = Dq;
-      p.lse2[(int64_t)h * p.T + tok] = lse2;
+      // negated and pre-divided so that the second kernel can seed its MFMA accumulators with them
+      p.dvec[(int64_t)h * p.T + tok] = -Dq;
+      p.lse2[(int64_t)h * p.T + tok] = -p.lse[(int64_t)h * p.T + tok] / p.scale;
     }
   }
 
@@ -213,26 +214,19 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
 #define ZP_SG_TRANS 0x400
 #define ZP_SG_DSREAD 0x100
 
+// P = exp2(c * (q.k - LSE/scale)) and dS = P * (dO.v - D): the row terms were seeded into the accumulators.
 template <int D, bool MASK>
-__device__ __forceinline__ void dkdv_pds(const f32x16 &s, const f32x16 &dp, const float *Lb, const float *Db, int qb,
-                                         int hi, int qpos0, int kpos, int qpos_end, float c_log2, bf16x8 (&pb)[2],
-                                         bf16x8 (&dsb)[2]) {
+__device__ __forceinline__ void dkdv_pds(const f32x16 &s, const f32x16 &dp, int qb, int hi, int qpos0, int kpos,
+                                         int qpos_end, float c_log2, bf16x8 (&pb)[2], bf16x8 (&dsb)[2]) {
 #pragma unroll
-  for (int b = 0; b < 4; b++) {
-    const f32x4 l4 = *(const ZP_LDS f32x4 *)((const ZP_LDS char *)Lb + (qb * 32 + 8 * b + 4 * hi) * 4);
-    const f32x4 d4 = *(const ZP_LDS f32x4 *)((const ZP_LDS char *)Db + (qb * 32 + 8 * b + 4 * hi) * 4);
-#pragma unroll
-    for (int c = 0; c < 4; c++) {
-      const int r = 4 * b + c;
-      float sv = s[r];
-      if (MASK) {
-        const int qpos = qpos0 + qb * 32 + 8 * b + 4 * hi + c;
-        if (qpos < kpos || qpos >= qpos_end) sv = -INFINITY;
-      }
-      const float pv = zp_exp2(__builtin_fmaf(sv, c_log2, -l4[c]));
-      pb[r >> 3][r & 7] = (__bf16)pv;
-      dsb[r >> 3][r & 7] = (__bf16)(pv * (dp[r] - d4[c]));
+  for (int r = 0; r < 16; r++) {
+    float pv = zp_exp2(s[r] * c_log2);
+    if (MASK) {
+      const int qpos = qpos0 + qb * 32 + 8 * (r >> 2) + 4 * hi + (r & 3);
+      if (qpos < kpos || qpos >= qpos_end) pv = 0.f;
     }
+    pb[r >> 3][r & 7] = (__bf16)pv;
+    dsb[r >> 3][r & 7] = (__bf16)(pv * dp[r]);
   }
 }
 
@@ -243,56 +237,74 @@ template <int D, bool MASK>
 __device__ __forceinline__ void dkdv_tile(const char *Qb, const char *Ob, const float *Lb, const float *Db,
                                           const bf16x8 (&kreg)[D / 16], const bf16x8 (&vreg)[D / 16],
                                           f32x16 (&dk_acc)[D / 32], f32x16 (&dv_acc)[D / 32], int qpos0, int kpos,
-                                          int qpos_end, float c_log2, int kl, int hi, int trow, int tcol) {
+                                          int qpos_end, float c_log2, int hi, const zp_lds_offsets<D> &lo) {
   constexpr int KK = D / 16, DB = D / 32;
   bf16x8 aq[KK], ao[KK];
   bf16x8 to[2][DB], tq[2][DB];
-  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  f32x16 s_seed[2], dp_seed[2];  // -LSE/scale and -D of the 16 query rows this lane holds, per block
 
+  auto load_seed = [&](int qb) {
+#pragma unroll
+    for (int b = 0; b < 4; b++) {
+      const f32x4 l4 = *(const ZP_LDS f32x4 *)((const ZP_LDS char *)Lb + (qb * 32 + 8 * b + 4 * hi) * 4);
+      const f32x4 d4 = *(const ZP_LDS f32x4 *)((const ZP_LDS char *)Db + (qb * 32 + 8 * b + 4 * hi) * 4);
+#pragma unroll
+      for (int c = 0; c < 4; c++) { s_seed[qb][4 * b + c] = l4[c]; dp_seed[qb][4 * b + c] = d4[c]; }
+    }
+  };
   auto load_rows = [&](int qb) {
 #pragma unroll
-    for (int kk = 0; kk < KK; kk++) aq[kk] = zp_lds_read16(Qb, zp_swz<D>(qb * 32 + kl, 2 * kk + hi));
+    for (int kk = 0; kk < KK; kk++) aq[kk] = lo.rows(Qb, qb, kk);
 #pragma unroll
-    for (int kk = 0; kk < KK; kk++) ao[kk] = zp_lds_read16(Ob, zp_swz<D>(qb * 32 + kl, 2 * kk + hi));
+    for (int kk = 0; kk < KK; kk++) ao[kk] = lo.rows(Ob, qb, kk);
   };
-  auto load_tr = [&](int qb) {
+  auto load_to = [&](int qb) {
 #pragma unroll
     for (int m = 0; m < 2; m++)
 #pragma unroll
-      for (int db = 0; db < DB; db++) {
-        to[m][db] = zp_cat(zp_lds_read_tr(Ob, zp_swz_col<D>(qb * 32 + m * 16 + trow, db * 32 + tcol)),
-                           zp_lds_read_tr(Ob, zp_swz_col<D>(qb * 32 + m * 16 + 8 + trow, db * 32 + tcol)));
-        tq[m][db] = zp_cat(zp_lds_read_tr(Qb, zp_swz_col<D>(qb * 32 + m * 16 + trow, db * 32 + tcol)),
-                           zp_lds_read_tr(Qb, zp_swz_col<D>(qb * 32 + m * 16 + 8 + trow, db * 32 + tcol)));
-      }
+      for (int db = 0; db < DB; db++) to[m][db] = lo.tr(Ob, qb, m, db);
+  };
+  auto load_tq = [&](int qb) {
+#pragma unroll
+    for (int m = 0; m < 2; m++)
+#pragma unroll
+      for (int db = 0; db < DB; db++) tq[m][db] = lo.tr(Qb, qb, m, db);
   };
 
+  load_seed(0);
   load_rows(0);
 #pragma unroll
   for (int qb = 0; qb < 2; qb++) {
     f32x16 s, dp;
-    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[0], kreg[0], zero, 0, 0, 0);
-    dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ao[0], vreg[0], zero, 0, 0, 0);
+    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[0], kreg[0], s_seed[qb], 0, 0, 0);
+    dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ao[0], vreg[0], dp_seed[qb], 0, 0, 0);
 #pragma unroll
     for (int kk = 1; kk < KK; kk++) {
       s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[kk], kreg[kk], s, 0, 0, 0);
       dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ao[kk], vreg[kk], dp, 0, 0, 0);
     }
     __builtin_amdgcn_sched_barrier(0);
-    load_tr(qb);
+    load_to(qb);                  // lands while P and dS are computed
+    if (qb == 0) load_seed(1);
     __builtin_amdgcn_sched_barrier(0);
     bf16x8 pb[2], dsb[2];
-    dkdv_pds<D, MASK>(s, dp, Lb, Db, qb, hi, qpos0, kpos, qpos_end, c_log2, pb, dsb);
+    dkdv_pds<D, MASK>(s, dp, qb, hi, qpos0, kpos, qpos_end, c_log2, pb, dsb);
     __builtin_amdgcn_sched_barrier(0);
-    if (qb == 0) load_rows(1);
+    load_tq(qb);                  // lands while dV accumulates
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int m = 0; m < 2; m++)
 #pragma unroll
-      for (int db = 0; db < DB; db++) {
+      for (int db = 0; db < DB; db++)
         dv_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(to[m][db], pb[m], dv_acc[db], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (qb == 0) load_rows(1);    // lands while dK accumulates
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int m = 0; m < 2; m++)
+#pragma unroll
+      for (int db = 0; db < DB; db++)
         dk_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq[m][db], dsb[m], dk_acc[db], 0, 0, 0);
-      }
     __builtin_amdgcn_sched_barrier(0);
   }
 }
@@ -305,8 +317,8 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
   extern __shared__ __attribute__((aligned(16))) char smem[];
   char *Qs = smem;                              // [NBUF][64][D]
   char *Os = smem + NBUF * TILEB;               // [NBUF][64][D]  (dO)
-  float *Ls = (float *)(smem + 2 * NBUF * TILEB);  // [NBUF][64] LSE * log2(e)
-  float *Ds = Ls + NBUF * 64;                   // [NBUF][64] D
+  float *Ls = (float *)(smem + 2 * NBUF * TILEB);  // [NBUF][64] -LSE / scale
+  float *Ds = Ls + NBUF * 64;                   // [NBUF][64] -D
 
   const int unit = blockIdx.x;
   if (unit >= p.n_kv_tiles * p.Hkv) return;
@@ -350,11 +362,16 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
   const int n_qt = (t.q_rows + 63) / 64;
   const int n_it = n_qt * p.grp;  // iterations: heads of the group outermost, query tiles innermost
 
+  zp_stager<D> qst, ost;
+  qst.init(p.q + (int64_t)t.q_tok0 * p.q_stride + (int64_t)g * p.grp * D, p.q_stride, tid);
+  ost.init(p.dout + (int64_t)t.q_tok0 * p.do_stride + (int64_t)g * p.grp * D, p.do_stride, tid);
+  zp_lds_offsets<D> lo;
+  lo.init(lane);
   auto stage = [&](int it, int buf) {
     const int hh = it / n_qt, i0 = (it - hh * n_qt) * 64;
     const int h = g * p.grp + hh;
-    zp_stage_async<D>(Qs + buf * TILEB, p.q + (int64_t)t.q_tok0 * p.q_stride + (int64_t)h * D, p.q_stride, i0, t.q_rows, tid);
-    zp_stage_async<D>(Os + buf * TILEB, p.dout + (int64_t)t.q_tok0 * p.do_stride + (int64_t)h * D, p.do_stride, i0, t.q_rows, tid);
+    qst.issue(Qs + buf * TILEB, i0, t.q_rows, (int64_t)hh * D);
+    ost.issue(Os + buf * TILEB, i0, t.q_rows, (int64_t)hh * D);
     const int64_t base = (int64_t)h * p.T + t.q_tok0;
     zp_stage_async_f32x64(Ls + buf * 64, p.lse2 + base, i0, t.q_rows - 1, lane);
     zp_stage_async_f32x64(Ds + buf * 64, p.dvec + base, i0, t.q_rows - 1, lane);
@@ -369,9 +386,6 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
   else zp_wait_async();
   __syncthreads();
 
-  const int g16 = lane >> 4, i16 = lane & 15;
-  const int trow = 4 * (g16 >> 1) + (i16 >> 2);
-  const int tcol = 16 * (g16 & 1) + 4 * (i16 & 3);
   const int kpos_w_min = t.k_pos0 + w * 32, kpos_w_max = t.k_pos0 + w * 32 + 31;
   const int qpos_end = t.q_pos0 + t.q_rows;
 
@@ -386,9 +400,9 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
       const char *Qb = Qs + buf * TILEB;
       const char *Ob = Os + buf * TILEB;
       if (qpos0 < kpos_w_max || qpos0 + 64 > qpos_end)
-        dkdv_tile<D, true>(Qb, Ob, Ls + buf * 64, Ds + buf * 64, kreg, vreg, dk_acc, dv_acc, qpos0, kpos, qpos_end, c_log2, kl, hi, trow, tcol);
+        dkdv_tile<D, true>(Qb, Ob, Ls + buf * 64, Ds + buf * 64, kreg, vreg, dk_acc, dv_acc, qpos0, kpos, qpos_end, c_log2, hi, lo);
       else
-        dkdv_tile<D, false>(Qb, Ob, Ls + buf * 64, Ds + buf * 64, kreg, vreg, dk_acc, dv_acc, qpos0, kpos, qpos_end, c_log2, kl, hi, trow, tcol);
+        dkdv_tile<D, false>(Qb, Ob, Ls + buf * 64, Ds + buf * 64, kreg, vreg, dk_acc, dv_acc, qpos0, kpos, qpos_end, c_log2, hi, lo);
     }
     // the next tile must have landed; the ones behind it may stay in flight
     if (ahead >= NBUF - 1) zp_wait_async_upto<(NBUF - 2) * LOADS>();

@@ -170,3 +170,98 @@ template <int N>
 __device__ __forceinline__ void zp_wait_async_upto() {
   __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
+
+// 16-byte direct-to-LDS load addressed as (wave-uniform 64-bit base) + (per-lane 32-bit byte offset)
+__device__ __forceinline__ void zp_dma16_so(const void *sbase_uniform, unsigned voff, unsigned lds_base_uniform) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1\n" ::"v"(voff), "s"(sbase_uniform),
+               "s"(lds_base_uniform)
+               : "memory");
+}
+__device__ __forceinline__ const void *zp_uniform_ptr(const void *p) {
+  unsigned long long v = (unsigned long long)p;
+  unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v), hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+  return (const void *)(((unsigned long long)hi << 32) | lo);
+}
+
+// Per-thread state of the asynchronous [64][D] tile copy: the lane's byte offsets inside a tile are worked
+// out once (they carry the LDS swizzle); issuing a tile is then scalar address arithmetic plus the loads.
+// `init` takes the tensor base of the row run and the token stride (64 * stride * 2 bytes must fit 32 bits);
+// `issue` copies rows row0 .. row0+63 (rows past rows_total clamp to the last valid row).
+template <int D>
+struct zp_stager {
+  static constexpr int PER_WAVE = 64 * D * 2 / 1024 / 4;  // 1 KiB wave-loads per wave (4 waves)
+  static constexpr int LOADS = PER_WAVE;
+  unsigned off[PER_WAVE];  // bytes from the tile's first row
+  int64_t stride;
+  const __bf16 *base;
+  int w, lane;
+  __device__ __forceinline__ static void row_chunk(int blk, int lane, int &r, int &c) {
+    if (D == 128) {
+      r = blk * 4 + (lane >> 4);
+      c = (lane & 15) ^ (((r & 3) << 2) | ((r >> 2) & 3));
+    } else {
+      r = blk * 8 + (lane >> 3);
+      c = (lane & 7) ^ (((r & 1) << 2) | ((r >> 1) & 3));
+    }
+  }
+  __device__ __forceinline__ void init(const __bf16 *gbase, int64_t tok_stride, int tid) {
+    lane = tid & 63;
+    w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    stride = tok_stride;
+    base = gbase;
+#pragma unroll
+    for (int n = 0; n < PER_WAVE; n++) {
+      int r, c;
+      row_chunk(w * PER_WAVE + n, lane, r, c);
+      off[n] = (unsigned)(((int64_t)r * tok_stride + c * 8) * 2);
+    }
+  }
+  // extra: a wave-uniform element offset added to every source address (e.g. head * D)
+  __device__ __forceinline__ void issue(char *lds_tile, int row0, int rows_total, int64_t extra = 0) const {
+    const unsigned lds0 = __builtin_amdgcn_readfirstlane(zp_lds_addr(lds_tile));
+    if (row0 + 64 <= rows_total) {
+      const void *sb = zp_uniform_ptr(base + (int64_t)row0 * stride + extra);
+#pragma unroll
+      for (int n = 0; n < PER_WAVE; n++) zp_dma16_so(sb, off[n], lds0 + (w * PER_WAVE + n) * 1024);
+    } else {
+#pragma unroll
+      for (int n = 0; n < PER_WAVE; n++) {
+        int r, c;
+        row_chunk(w * PER_WAVE + n, lane, r, c);
+        int gr = row0 + r;
+        if (gr > rows_total - 1) gr = rows_total - 1;
+        zp_dma16(base + (int64_t)gr * stride + c * 8 + extra, lds0 + (w * PER_WAVE + n) * 1024);
+      }
+    }
+  }
+};
+
+// LDS read offsets of one lane for the two MFMA operand patterns of a [64][D] zp_swz tile, worked out once.
+// rows(kb, kk): 16 bytes of row 32*kb + (lane%32), head-dim elements 16*kk + 8*(lane/32) ..+7  (row-major operand)
+// tr(kb, m, j, db): transposed 4-row piece for k-slots 4j..4j+3 of MFMA m of 32-row block kb, columns 32*db + lane%32
+template <int D>
+struct zp_lds_offsets {
+  int row_off[D / 16];      // + kb * 32 * ROWB
+  int tr_off[2][D / 32];    // [j][db], + (kb * 32 + m * 16) * ROWB
+  static constexpr int ROWB = D * 2;
+  __device__ __forceinline__ void init(int lane) {
+    const int r32 = lane & 31, hi = lane >> 5;
+#pragma unroll
+    for (int kk = 0; kk < D / 16; kk++) row_off[kk] = zp_swz<D>(r32, 2 * kk + hi);
+    const int g16 = lane >> 4, i16 = lane & 15;
+    const int trow = 4 * (g16 >> 1) + (i16 >> 2);
+    const int tcol = 16 * (g16 & 1) + 4 * (i16 & 3);
+#pragma unroll
+    for (int j = 0; j < 2; j++)
+#pragma unroll
+      for (int db = 0; db < D / 32; db++) tr_off[j][db] = zp_swz_col<D>(8 * j + trow, db * 32 + tcol);
+  }
+  // the swizzle depends on row % 16 only (D = 128) / row % 8 (D = 64), so blocks of 32 and 16 rows shift by a constant
+  __device__ __forceinline__ bf16x8 rows(const char *tile, int kb, int kk) const {
+    return zp_lds_read16(tile, row_off[kk] + kb * 32 * ROWB);
+  }
+  __device__ __forceinline__ bf16x8 tr(const char *tile, int kb, int m, int db) const {
+    const int o = (kb * 32 + m * 16) * ROWB;
+    return zp_cat(zp_lds_read_tr(tile, tr_off[0][db] + o), zp_lds_read_tr(tile, tr_off[1][db] + o));
+  }
+};
