@@ -367,9 +367,12 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
   ost.init(p.dout + (int64_t)t.q_tok0 * p.do_stride + (int64_t)g * p.grp * D, p.do_stride, tid);
   zp_lds_offsets<D> lo;
   lo.init(lane);
-  auto stage = [&](int it, int buf) {
-    const int hh = it / n_qt, i0 = (it - hh * n_qt) * 64;
+  // (head in group, query tile) of the next tile to stage and of the tile being computed, advanced in step
+  int st_hh = 0, st_qt = 0;
+  auto stage = [&](int buf) {
+    const int hh = st_hh, i0 = st_qt * 64;
     const int h = g * p.grp + hh;
+    if (++st_qt == n_qt) { st_qt = 0; st_hh++; }
     qst.issue(Qs + buf * TILEB, i0, t.q_rows, (int64_t)hh * D);
     ost.issue(Os + buf * TILEB, i0, t.q_rows, (int64_t)hh * D);
     const int64_t base = (int64_t)h * p.T + t.q_tok0;
@@ -378,9 +381,9 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
   };
 
   // prologue: up to NBUF-1 tiles in flight; tile 0 must have landed before the first iteration
-  if (n_it > 0) stage(0, 0);
-  if (n_it > 1) stage(1, 1);
-  if (n_it > 2) stage(2, 2);
+  if (n_it > 0) stage(0);
+  if (n_it > 1) stage(1);
+  if (n_it > 2) stage(2);
   if (n_it > 2) zp_wait_async_upto<2 * LOADS>();
   else if (n_it > 1) zp_wait_async_upto<LOADS>();
   else zp_wait_async();
@@ -389,11 +392,12 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
   const int kpos_w_min = t.k_pos0 + w * 32, kpos_w_max = t.k_pos0 + w * 32 + 31;
   const int qpos_end = t.q_pos0 + t.q_rows;
 
-  int buf = 0;
+  int buf = 0, cur_qt = 0;
   for (int it = 0; it < n_it; it++) {
-    const int hh = it / n_qt, i0 = (it - hh * n_qt) * 64;
+    const int i0 = cur_qt * 64;
+    if (++cur_qt == n_qt) cur_qt = 0;
     const int ahead = n_it - 1 - it;  // tiles after this one
-    if (ahead >= NBUF - 1) stage(it + NBUF - 1, (buf + NBUF - 1) & (NBUF - 1));
+    if (ahead >= NBUF - 1) stage((buf + NBUF - 1) & (NBUF - 1));
 
     const int qpos0 = t.q_pos0 + i0;  // position of the tile's first query
     if (qpos0 + 63 >= kpos_w_min) {   // otherwise every query of the tile precedes every key of this wave
