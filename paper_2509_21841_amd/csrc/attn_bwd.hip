@@ -61,10 +61,58 @@ __device__ __forceinline__ void store_acc_rows(__bf16 *dst, const f32x16 (&acc)[
     }
 }
 
+#define ZP_SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
+#define ZP_SG_MFMA 0x008
+#define ZP_SG_VALU 0x002
+#define ZP_SG_TRANS 0x400
+#define ZP_SG_DSREAD 0x100
+
 // ------------------------------------------------------------------------------------------- dQ
+// One 32-key half of a K/V tile for one wave: S^T and dP^T chains, dS^T, then dQ^T += K^T dS^T.
+template <int D, bool MASK>
+__device__ __forceinline__ void dq_half(const char *Kb, const char *Vb, int kb, const bf16x8 (&qreg)[D / 16],
+                                        const bf16x8 (&doreg)[D / 16], f32x16 (&dq_acc)[D / 32], float c_log2,
+                                        float lse2, float Dq, int j0, int hi, int nvis_lane,
+                                        const zp_lds_offsets<D> &lo) {
+  constexpr int KK = D / 16, DB = D / 32;
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  f32x16 s = zero, dp = zero;
+#pragma unroll
+  for (int kk = 0; kk < KK; kk++) {
+    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo.rows(Kb, kb, kk), qreg[kk], s, 0, 0, 0);
+    dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo.rows(Vb, kb, kk), doreg[kk], dp, 0, 0, 0);
+  }
+  // keep the LDS operand reads only a step ahead of the MFMAs that use them (register budget of two waves per SIMD)
+  ZP_SGB(ZP_SG_DSREAD, 4);
+#pragma unroll
+  for (int kk = 0; kk < KK - 2; kk++) {
+    ZP_SGB(ZP_SG_MFMA, 2);
+    ZP_SGB(ZP_SG_DSREAD, 2);
+  }
+  ZP_SGB(ZP_SG_MFMA, 4);
+  __builtin_amdgcn_sched_barrier(0);
+  bf16x8 dsb[2];
+#pragma unroll
+  for (int r = 0; r < 16; r++) {
+    float pv = zp_exp2(__builtin_fmaf(s[r], c_log2, -lse2));
+    if (MASK) {
+      const int j = j0 + kb * 32 + 8 * (r >> 2) + 4 * hi + (r & 3);
+      if (j >= nvis_lane) pv = 0.f;
+    }
+    dsb[r >> 3][r & 7] = (__bf16)(pv * (dp[r] - Dq));
+  }
+#pragma unroll
+  for (int m = 0; m < 2; m++)
+#pragma unroll
+    for (int db = 0; db < DB; db++)
+      dq_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo.tr(Kb, kb, m, db), dsb[m], dq_acc[db], 0, 0, 0);
+  __builtin_amdgcn_sched_barrier(0);
+}
+
 template <int D>
 __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void attn_bwd_dq_kernel(zp_bwd_params p) {
   constexpr int TILEB = 64 * D * 2;
+  constexpr int LOADS = 2 * zp_stager<D>::LOADS;  // async loads one wave issues per staged K/V tile pair
   extern __shared__ __attribute__((aligned(16))) char smem[];
   char *Ks = smem;               // [2][64][D]
   char *Vs = smem + 2 * TILEB;   // [2][64][D]
@@ -113,17 +161,22 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
   const float Dq = zp_pair_sum(dsum);
   float lse2 = 0.f;
   if (row_ok) {
-    lse2 = p.lse[(int64_t)h * p.T + tok] * LOG2E;
+    const float lse_nat = p.lse[(int64_t)h * p.T + tok];
+    lse2 = lse_nat * LOG2E;
     if (hi == 0) {
       // negated and pre-divided so that the second kernel can seed its MFMA accumulators with them
       p.dvec[(int64_t)h * p.T + tok] = -Dq;
-      p.lse2[(int64_t)h * p.T + tok] = -p.lse[(int64_t)h * p.T + tok] / p.scale;
+      p.lse2[(int64_t)h * p.T + tok] = -lse_nat / p.scale;
     }
   }
+  // every register operand has arrived before the first asynchronous tile copy is issued
+  zp_wait_async();
 
-  const __bf16 *kbase = p.k + (int64_t)t.k_tok0 * p.k_stride + (int64_t)g * D;
-  const __bf16 *vbase = p.v + (int64_t)t.k_tok0 * p.v_stride + (int64_t)g * D;
-  TileStage<D> kst, vst;
+  zp_stager<D> kst, vst;
+  kst.init(p.k + (int64_t)t.k_tok0 * p.k_stride + (int64_t)g * D, p.k_stride, tid);
+  vst.init(p.v + (int64_t)t.k_tok0 * p.v_stride + (int64_t)g * D, p.v_stride, tid);
+  zp_lds_offsets<D> lo;
+  lo.init(lane);
 
   f32x16 dq_acc[D / 32];
 #pragma unroll
@@ -133,67 +186,31 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
   const float c_log2 = p.scale_log2;
 
   if (n_kt > 0) {
-    kst.load(kbase, p.k_stride, 0, t.k_len, tid);
-    vst.load(vbase, p.v_stride, 0, t.k_len, tid);
-    kst.store(Ks, tid);
-    vst.store(Vs, tid);
+    kst.issue(Ks, 0, t.k_len);
+    vst.issue(Vs, 0, t.k_len);
   }
+  zp_wait_async();
   __syncthreads();
-
-  const int g16 = lane >> 4, i16 = lane & 15;
-  const int trow = 4 * (g16 >> 1) + (i16 >> 2);
-  const int tcol = 16 * (g16 & 1) + 4 * (i16 & 3);
 
   for (int it = 0; it < n_kt; it++) {
     const int j0 = it * 64, buf = it & 1;
-    if (it + 1 < n_kt) {
-      kst.load(kbase, p.k_stride, j0 + 64, t.k_len, tid);
-      vst.load(vbase, p.v_stride, j0 + 64, t.k_len, tid);
+    const bool more = it + 1 < n_kt;
+    if (more) {
+      kst.issue(Ks + (buf ^ 1) * TILEB, j0 + 64, t.k_len);
+      vst.issue(Vs + (buf ^ 1) * TILEB, j0 + 64, t.k_len);
     }
     if (j0 < nvis_w_max) {
       const char *Kb = Ks + buf * TILEB;
       const char *Vb = Vs + buf * TILEB;
-      const bool need_mask = j0 + 64 > nvis_w_min;
-#pragma unroll
-      for (int kb = 0; kb < 2; kb++) {
-        f32x16 s, dp;
-#pragma unroll
-        for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = 0.f; }
-#pragma unroll
-        for (int kk = 0; kk < D / 16; kk++) {
-          bf16x8 a = zp_lds_read16(Kb, zp_swz<D>(kb * 32 + ql, 2 * kk + hi));
-          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[kk], s, 0, 0, 0);
-        }
-#pragma unroll
-        for (int kk = 0; kk < D / 16; kk++) {
-          bf16x8 a = zp_lds_read16(Vb, zp_swz<D>(kb * 32 + ql, 2 * kk + hi));
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, doreg[kk], dp, 0, 0, 0);
-        }
-        bf16x8 dsb[2];
-#pragma unroll
-        for (int r = 0; r < 16; r++) {
-          float sv = s[r];
-          if (need_mask) {
-            int j = j0 + kb * 32 + 8 * (r >> 2) + 4 * hi + (r & 3);
-            if (j >= nvis_lane) sv = -INFINITY;
-          }
-          float pv = zp_exp2(__builtin_fmaf(sv, c_log2, -lse2));
-          dsb[r >> 3][r & 7] = (__bf16)(pv * (dp[r] - Dq));
-        }
-#pragma unroll
-        for (int m = 0; m < 2; m++)
-#pragma unroll
-          for (int db = 0; db < D / 32; db++) {
-            bf16x4 lo = zp_lds_read_tr(Kb, zp_swz_col<D>(kb * 32 + m * 16 + trow, db * 32 + tcol));
-            bf16x4 hi4 = zp_lds_read_tr(Kb, zp_swz_col<D>(kb * 32 + m * 16 + 8 + trow, db * 32 + tcol));
-            dq_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zp_cat(lo, hi4), dsb[m], dq_acc[db], 0, 0, 0);
-          }
+      if (j0 + 64 > nvis_w_min) {
+        dq_half<D, true>(Kb, Vb, 0, qreg, doreg, dq_acc, c_log2, lse2, Dq, j0, hi, nvis_lane, lo);
+        dq_half<D, true>(Kb, Vb, 1, qreg, doreg, dq_acc, c_log2, lse2, Dq, j0, hi, nvis_lane, lo);
+      } else {
+        dq_half<D, false>(Kb, Vb, 0, qreg, doreg, dq_acc, c_log2, lse2, Dq, j0, hi, nvis_lane, lo);
+        dq_half<D, false>(Kb, Vb, 1, qreg, doreg, dq_acc, c_log2, lse2, Dq, j0, hi, nvis_lane, lo);
       }
     }
-    if (it + 1 < n_kt) {
-      kst.store(Ks + (buf ^ 1) * TILEB, tid);
-      vst.store(Vs + (buf ^ 1) * TILEB, tid);
-    }
+    zp_wait_async();
     __syncthreads();
   }
 
@@ -208,11 +225,6 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
 // two), so latency is hidden inside the wave: per 64-query tile the two 32-query blocks are software
 // pipelined -- LDS operands are fetched a phase ahead, the exp/scale arithmetic of one block is interleaved
 // with the MFMAs of the other.
-#define ZP_SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
-#define ZP_SG_MFMA 0x008
-#define ZP_SG_VALU 0x002
-#define ZP_SG_TRANS 0x400
-#define ZP_SG_DSREAD 0x100
 
 // P = exp2(c * (q.k - LSE/scale)) and dS = P * (dO.v - D): the row terms were seeded into the accumulators.
 template <int D, bool MASK>
