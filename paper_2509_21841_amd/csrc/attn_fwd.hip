@@ -12,24 +12,80 @@
 namespace {
 
 constexpr int BN = 64;  // keys per LDS tile
+#define ZP_SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
+#define ZP_SG_MFMA 0x008
+#define ZP_SG_DSREAD 0x100
 
 template <int D, int NW>
 struct FwdCfg {
   static constexpr int NT = NW * 64;
   static constexpr int BM = NW * 32;
-  static constexpr int ROWB = D * 2;                   // bytes per tile row
-  static constexpr int TILEB = BN * ROWB;              // bytes per K (or V) tile
-  static constexpr int CHUNKS = BN * D / 8;            // 16-byte chunks per tile
-  static constexpr int CPT = CHUNKS / NT;              // chunks per thread
-  static_assert(CHUNKS % NT == 0, "tile chunks must divide over the threads");
+  static constexpr int TILEB = BN * D * 2;  // bytes per K (or V) tile
 };
+
+// One 64-key tile for one wave of 32 query rows.
+template <int D, bool MASK>
+__device__ __forceinline__ void fwd_tile(const char *Kb, const char *Vb, const bf16x8 (&qreg)[D / 16],
+                                         f32x16 (&o_acc)[D / 32], float &mc, float &l_sum, float c_log2, int j0,
+                                         int hi, int nvis_lane, const zp_lds_offsets<D> &lo) {
+  constexpr int KK = D / 16, DB = D / 32;
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  f32x16 s0 = zero, s1 = zero;
+#pragma unroll
+  for (int kk = 0; kk < KK; kk++) {
+    s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo.rows(Kb, 0, kk), qreg[kk], s0, 0, 0, 0);
+    s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo.rows(Kb, 1, kk), qreg[kk], s1, 0, 0, 0);
+  }
+  if (MASK) {
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+      const int j = j0 + 8 * (r >> 2) + 4 * hi + (r & 3);
+      if (j >= nvis_lane) s0[r] = -INFINITY;
+      if (j + 32 >= nvis_lane) s1[r] = -INFINITY;
+    }
+  }
+  float tmax = fmaxf(s0[0], s1[0]);
+#pragma unroll
+  for (int r = 1; r < 16; r++) tmax = fmaxf(tmax, fmaxf(s0[r], s1[r]));
+  tmax = zp_pair_max(tmax);
+  const float tmc = tmax * c_log2;
+  // the reference maximum moves only when the tile maximum exceeds it by more than 2^8
+  if (__builtin_amdgcn_ballot_w64(tmc > mc + 8.0f) != 0) {
+    const bool mv = tmc > mc + 8.0f;
+    const float alpha = mv ? zp_exp2(mc - tmc) : 1.0f;
+    mc = mv ? tmc : mc;
+    l_sum *= alpha;
+#pragma unroll
+    for (int i = 0; i < DB; i++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) o_acc[i][r] *= alpha;
+  }
+  const float neg_mc = (mc == -INFINITY) ? 0.f : -mc;
+  bf16x8 pb[2][2];
+#pragma unroll
+  for (int r = 0; r < 16; r++) {
+    const float p0 = zp_exp2(__builtin_fmaf(s0[r], c_log2, neg_mc));
+    const float p1 = zp_exp2(__builtin_fmaf(s1[r], c_log2, neg_mc));
+    l_sum += p0 + p1;
+    pb[0][r >> 3][r & 7] = (__bf16)p0;
+    pb[1][r >> 3][r & 7] = (__bf16)p1;
+  }
+#pragma unroll
+  for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+    for (int m = 0; m < 2; m++)
+#pragma unroll
+      for (int db = 0; db < DB; db++)
+        o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo.tr(Vb, kb, m, db), pb[kb][m], o_acc[db], 0, 0, 0);
+}
 
 template <int D, int NW, bool PARTIAL>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_fwd_kernel(zp_attn_params p) {
   using C = FwdCfg<D, NW>;
+  static_assert(NW == 4, "the tile stager is laid out for four waves");
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  char *Ks = smem;                  // [2][BN][D] bf16, row-read swizzle
-  char *Vs = smem + 2 * C::TILEB;   // [2][BN][D] bf16, transposed-read swizzle
+  char *Ks = smem;                  // [2][BN][D] bf16
+  char *Vs = smem + 2 * C::TILEB;   // [2][BN][D] bf16
 
   int unit, hh;
   zp_block_to_unit(blockIdx.x, p.grp, unit, hh);
@@ -50,8 +106,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   };
   const int nvis_lane = nvis_of(row);
   const int nvis_w_min = nvis_of(w * 32), nvis_w_max = nvis_of(w * 32 + 31);
-  const int nvis_blk = nvis_of(t.q_rows - 1);
-  const int n_kt = (nvis_blk + BN - 1) / BN;
+  const int n_kt = (nvis_of(t.q_rows - 1) + BN - 1) / BN;
 
   // Q^T operand: 8 consecutive head-dim elements of this lane's query per 16-wide k-step
   bf16x8 qreg[D / 16];
@@ -63,32 +118,14 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       else qreg[kk] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
     }
   }
+  // the register operands have arrived before the first asynchronous tile copy is issued
+  zp_wait_async();
 
-  const __bf16 *kbase = p.k + (int64_t)t.k_tok0 * p.k_stride + (int64_t)g * D;
-  const __bf16 *vbase = p.v + (int64_t)t.k_tok0 * p.v_stride + (int64_t)g * D;
-
-  u32x4 kpre[C::CPT], vpre[C::CPT];
-  auto load_tile = [&](int j0) {
-#pragma unroll
-    for (int n = 0; n < C::CPT; n++) {
-      int id = tid + n * C::NT, r = id / (D / 8), c = id % (D / 8);
-      if (j0 + r < t.k_len) {
-        kpre[n] = *(const u32x4 *)(kbase + (int64_t)(j0 + r) * p.k_stride + c * 8);
-        vpre[n] = *(const u32x4 *)(vbase + (int64_t)(j0 + r) * p.v_stride + c * 8);
-      } else {
-        kpre[n] = u32x4{0, 0, 0, 0};
-        vpre[n] = u32x4{0, 0, 0, 0};
-      }
-    }
-  };
-  auto store_tile = [&](int buf) {
-#pragma unroll
-    for (int n = 0; n < C::CPT; n++) {
-      int id = tid + n * C::NT, r = id / (D / 8), c = id % (D / 8);
-      zp_lds_write16(Ks + buf * C::TILEB, zp_koff<D>(r, c), kpre[n]);
-      zp_lds_write16(Vs + buf * C::TILEB, zp_voff<D>(r, c * 8), vpre[n]);
-    }
-  };
+  zp_stager<D> kst, vst;
+  kst.init(p.k + (int64_t)t.k_tok0 * p.k_stride + (int64_t)g * D, p.k_stride, tid);
+  vst.init(p.v + (int64_t)t.k_tok0 * p.v_stride + (int64_t)g * D, p.v_stride, tid);
+  zp_lds_offsets<D> lo;
+  lo.init(lane);
 
   f32x16 o_acc[D / 32];
 #pragma unroll
@@ -100,82 +137,25 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const float c_log2 = p.scale_log2;
 
   if (n_kt > 0) {
-    load_tile(0);
-    store_tile(0);
+    kst.issue(Ks, 0, t.k_len);
+    vst.issue(Vs, 0, t.k_len);
   }
+  zp_wait_async();
   __syncthreads();
 
   for (int it = 0; it < n_kt; it++) {
     const int j0 = it * BN, buf = it & 1;
-    if (it + 1 < n_kt) load_tile(j0 + BN);
-
+    if (it + 1 < n_kt) {
+      kst.issue(Ks + (buf ^ 1) * C::TILEB, j0 + BN, t.k_len);
+      vst.issue(Vs + (buf ^ 1) * C::TILEB, j0 + BN, t.k_len);
+    }
     if (j0 < nvis_w_max) {  // otherwise every key of this tile is masked for the whole wave
       const char *Kb = Ks + buf * C::TILEB;
       const char *Vb = Vs + buf * C::TILEB;
-      f32x16 s_acc[2];
-#pragma unroll
-      for (int kb = 0; kb < 2; kb++) {
-#pragma unroll
-        for (int r = 0; r < 16; r++) s_acc[kb][r] = 0.f;
-#pragma unroll
-        for (int kk = 0; kk < D / 16; kk++) {
-          bf16x8 a = zp_lds_read16(Kb, zp_koff<D>(kb * 32 + ql, 2 * kk + hi));
-          s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[kk], s_acc[kb], 0, 0, 0);
-        }
-      }
-      if (j0 + BN > nvis_w_min) {  // some lane has a masked key in this tile
-#pragma unroll
-        for (int kb = 0; kb < 2; kb++)
-#pragma unroll
-          for (int r = 0; r < 16; r++) {
-            int j = j0 + kb * 32 + 8 * (r >> 2) + 4 * hi + (r & 3);
-            if (j >= nvis_lane) s_acc[kb][r] = -INFINITY;
-          }
-      }
-      float tmax = s_acc[0][0];
-#pragma unroll
-      for (int r = 1; r < 16; r++) tmax = fmaxf(tmax, s_acc[0][r]);
-#pragma unroll
-      for (int r = 0; r < 16; r++) tmax = fmaxf(tmax, s_acc[1][r]);
-      tmax = zp_pair_max(tmax);
-      const float tmc = tmax * c_log2;
-      // the reference maximum moves only when the tile maximum exceeds it by more than 2^8
-      if (__builtin_amdgcn_ballot_w64(tmc > mc + 8.0f) != 0) {
-        const bool mv = tmc > mc + 8.0f;
-        const float alpha = mv ? zp_exp2(mc - tmc) : 1.0f;
-        mc = mv ? tmc : mc;
-        l_sum *= alpha;
-#pragma unroll
-        for (int i = 0; i < D / 32; i++)
-#pragma unroll
-          for (int r = 0; r < 16; r++) o_acc[i][r] *= alpha;
-      }
-      const float neg_mc = (mc == -INFINITY) ? 0.f : -mc;
-      bf16x8 pb[2][2];
-#pragma unroll
-      for (int kb = 0; kb < 2; kb++)
-#pragma unroll
-        for (int r = 0; r < 16; r++) {
-          float pv = zp_exp2(__builtin_fmaf(s_acc[kb][r], c_log2, neg_mc));
-          l_sum += pv;
-          pb[kb][r >> 3][r & 7] = (__bf16)pv;
-        }
-      const int g16 = lane >> 4, i16 = lane & 15;
-      const int vrow = 4 * (g16 >> 1) + (i16 >> 2);           // + 32kb + 16m + 8j
-      const int vcol = 16 * (g16 & 1) + 4 * (i16 & 3);        // + 32 dblk
-#pragma unroll
-      for (int kb = 0; kb < 2; kb++)
-#pragma unroll
-        for (int m = 0; m < 2; m++)
-#pragma unroll
-          for (int db = 0; db < D / 32; db++) {
-            bf16x4 lo = zp_lds_read_tr(Vb, zp_voff<D>(kb * 32 + m * 16 + vrow, db * 32 + vcol));
-            bf16x4 hi4 = zp_lds_read_tr(Vb, zp_voff<D>(kb * 32 + m * 16 + 8 + vrow, db * 32 + vcol));
-            o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zp_cat(lo, hi4), pb[kb][m], o_acc[db], 0, 0, 0);
-          }
+      if (j0 + BN > nvis_w_min) fwd_tile<D, true>(Kb, Vb, qreg, o_acc, mc, l_sum, c_log2, j0, hi, nvis_lane, lo);
+      else fwd_tile<D, false>(Kb, Vb, qreg, o_acc, mc, l_sum, c_log2, j0, hi, nvis_lane, lo);
     }
-
-    if (it + 1 < n_kt) store_tile(buf ^ 1);
+    zp_wait_async();
     __syncthreads();
   }
 
