@@ -12,7 +12,7 @@ struct zp_merge_dev {
 struct zp_merge_item { int32_t merge, row0; };  // a band of up to MERGE_ROWS rows of one merge
 
 namespace {
-constexpr int MERGE_NT = 256;
+constexpr int MERGE_NT = 512;
 constexpr int MERGE_ROWS = 8;
 
 __global__ __launch_bounds__(MERGE_NT) void lse_merge_kernel(const float *__restrict__ o_part, const float *__restrict__ lse_part,
@@ -31,14 +31,19 @@ __global__ __launch_bounds__(MERGE_NT) void lse_merge_kernel(const float *__rest
     const int r = w / per_row, rem = w - r * per_row;
     const int h = rem / d4, c4 = rem - h * d4;
     const int rr = it.row0 + r;
+    // all loads of the item are issued before any arithmetic: n_parts LSEs and n_parts float4 in flight
     float lp[ZP_MAX_PARTS];
-    float mx = -INFINITY;
+    f32x4 v[ZP_MAX_PARTS];
 #pragma unroll
     for (int p = 0; p < ZP_MAX_PARTS; p++)
       if (p < mg.n_parts) {
         lp[p] = lse_part[(int64_t)h * part_rows + mg.part_row0[p] + rr];
-        mx = fmaxf(mx, lp[p]);
+        v[p] = __builtin_nontemporal_load((const f32x4 *)(o_part + ((int64_t)(mg.part_row0[p] + rr) * Hq + h) * d) + c4);
       }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int p = 0; p < ZP_MAX_PARTS; p++)
+      if (p < mg.n_parts) mx = fmaxf(mx, lp[p]);
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     float L = -INFINITY;
     if (mx != -INFINITY) {
@@ -49,12 +54,7 @@ __global__ __launch_bounds__(MERGE_NT) void lse_merge_kernel(const float *__rest
       L = mx + __logf(sum);
 #pragma unroll
       for (int p = 0; p < ZP_MAX_PARTS; p++)
-        if (p < mg.n_parts && lp[p] != -INFINITY) {
-          const float wgt = __expf(lp[p] - L);
-          const f32x4 v = __builtin_nontemporal_load(
-              (const f32x4 *)(o_part + ((int64_t)(mg.part_row0[p] + rr) * Hq + h) * d) + c4);
-          acc += wgt * v;
-        }
+        if (p < mg.n_parts && lp[p] != -INFINITY) acc += __expf(lp[p] - L) * v[p];
     }
     const int64_t t = (int64_t)mg.out_tok0 + rr;
     bf16x4 ob = {(__bf16)acc[0], (__bf16)acc[1], (__bf16)acc[2], (__bf16)acc[3]};

@@ -5,7 +5,7 @@
 
 namespace {
 
-constexpr int REMAP_NT = 256;
+constexpr int REMAP_NT = 1024;  // measured best on MI355X: 1024 threads, 4 x 16 B in flight per thread
 constexpr int REMAP_UNROLL = 4;
 
 // chunks_per_row = row_bytes / 16. Each block handles `rows_per_block` index entries.
@@ -52,8 +52,8 @@ extern "C" int zp_launch_remap(const void *src, void *dst, int64_t row_bytes, co
   const int cpr = (int)(row_bytes / 16);
   int shift = -1;
   if ((cpr & (cpr - 1)) == 0) { shift = 0; while ((1 << shift) < cpr) shift++; }
-  // about 64 KiB per block, at least one row
-  int rpb = (int)(65536 / row_bytes);
+  // 64 KiB per block for short rows, 128 KiB for long ones (measured), at least one row
+  int rpb = (int)((row_bytes <= 4096 ? 65536 : 131072) / row_bytes);
   if (rpb < 1) rpb = 1;
   const int64_t grid = (n_rows + rpb - 1) / rpb;
   const u32x4 *s = (const u32x4 *)src;
