@@ -372,19 +372,21 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
   const float c_log2 = p.scale_log2;
 
   const int n_qt = (t.q_rows + 63) / 64;
-  const int n_it = n_qt * p.grp;  // iterations: heads of the group outermost, query tiles innermost
+  const int n_it = n_qt * p.grp;  // iterations: query tiles outermost (last tile first), heads of the group innermost
 
   zp_stager<D> qst, ost;
   qst.init(p.q + (int64_t)t.q_tok0 * p.q_stride + (int64_t)g * p.grp * D, p.q_stride, tid);
   ost.init(p.dout + (int64_t)t.q_tok0 * p.do_stride + (int64_t)g * p.grp * D, p.do_stride, tid);
   zp_lds_offsets<D> lo;
   lo.init(lane);
-  // (head in group, query tile) of the next tile to stage and of the tile being computed, advanced in step
-  int st_hh = 0, st_qt = 0;
+  // Iteration order: query tiles from the END of the sequence backwards, the heads of the group innermost.
+  // Workgroups of one sequence that start together then read the same (tile, head) at the same time and
+  // share it in L2; the diagonal (masked) tiles come last.
+  int st_hh = 0, st_qt = n_qt - 1;
   auto stage = [&](int buf) {
     const int hh = st_hh, i0 = st_qt * 64;
     const int h = g * p.grp + hh;
-    if (++st_qt == n_qt) { st_qt = 0; st_hh++; }
+    if (++st_hh == p.grp) { st_hh = 0; st_qt--; }
     qst.issue(Qs + buf * TILEB, i0, t.q_rows, (int64_t)hh * D);
     ost.issue(Os + buf * TILEB, i0, t.q_rows, (int64_t)hh * D);
     const int64_t base = (int64_t)h * p.T + t.q_tok0;
@@ -404,10 +406,10 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
   const int kpos_w_min = t.k_pos0 + w * 32, kpos_w_max = t.k_pos0 + w * 32 + 31;
   const int qpos_end = t.q_pos0 + t.q_rows;
 
-  int buf = 0, cur_qt = 0;
+  int buf = 0, cur_qt = n_qt - 1, cur_hh = 0;
   for (int it = 0; it < n_it; it++) {
     const int i0 = cur_qt * 64;
-    if (++cur_qt == n_qt) cur_qt = 0;
+    if (++cur_hh == p.grp) { cur_hh = 0; cur_qt--; }
     const int ahead = n_it - 1 - it;  // tiles after this one
     if (ahead >= NBUF - 1) stage((buf + NBUF - 1) & (NBUF - 1));
 
