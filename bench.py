@@ -27,6 +27,10 @@ from paper_2509_21841_amd import synth  # noqa: E402
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
 HBM_PEAK_GBPS = 8000.0
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script on the default workload,
+# scaled by what the same counters read for a copy of known size (profiles/bench_longtail-128k-gqa32x8_hbm_traffic.txt)
+MEASURED_TRAFFIC_BYTES = {("longtail-128k-gqa32x8", "attn_bwd_dkdv"): (7605301 * 2.00 + 524615 * 1.00) * 1024,
+                          ("longtail-128k-gqa32x8", "attn_bwd_dq"): (5466610 * 2.00 + 1082819 * 1.00) * 1024}
 
 WORKLOADS = {
     # name: (T, Hq, Hkv, d, seed, length recipe, chunks for long sequences, backward?, remap?)
@@ -209,7 +213,7 @@ def main():
     dom = max(attn, key=lambda k: attn[k]["ms_per_step"])
     ach = kernel_flops(job, dom) / (kern[dom]["avg_ms"] * 1e-3) / 1e12
     roofline = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
+                "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": MEASURED_TRAFFIC_BYTES.get((a.workload, dom))}
     total_flops = job.flops_fwd + job.flops_bwd
     value = total_flops / (ms_step * 1e-3) / 1e12
     out = {
