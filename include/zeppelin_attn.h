@@ -13,7 +13,8 @@
  *  - `ws` is caller-provided device scratch of at least zp_workspace_bytes(...) bytes, 256-byte aligned.
  *    Its contents are undefined afterwards. Two calls that share one `ws` must be ordered on one stream.
  *  - Layouts: token-major packed tensors. Q, O, dO, dQ are [T][Hq][d]; K, V, dK, dV are [T][Hkv][d],
- *    bfloat16, head stride d, with an explicit token stride in ELEMENTS (so a fused QKV buffer works).
+ *    bfloat16, head stride d, with an explicit token stride in ELEMENTS (so a fused QKV buffer works;
+ *    a multiple of 8, at least H*d and at most 2^24).
  *    LSE is float32 [Hq][T], natural logarithm. Q head h reads KV head h / (Hq/Hkv).
  *  - Sequence s owns tokens cu_seqlens[s] .. cu_seqlens[s+1]-1; cu_seqlens[0] = 0, non-decreasing,
  *    cu_seqlens[S] = T. Zero-length sequences are legal. A token attends only to tokens of its own

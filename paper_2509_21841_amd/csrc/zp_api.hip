@@ -138,7 +138,11 @@ int check_cu(const int32_t *cu, const zp_shape *sh) {
   if (cu[sh->S] != sh->T) return ZP_EINVAL;
   return ZP_OK;
 }
-int check_stride(int64_t stride, int H, int d) { return (stride < (int64_t)H * d || (stride % 8)) ? ZP_EINVAL : ZP_OK; }
+// token strides: at least one token's heads, 16-byte aligned rows, and small enough that the byte offsets of a
+// 64-row tile fit the 32-bit lane offsets of the asynchronous tile copy
+int check_stride(int64_t stride, int H, int d) {
+  return (stride < (int64_t)H * d || (stride % 8) || stride > (1 << 24)) ? ZP_EINVAL : ZP_OK;
+}
 bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
 int check_ws(const void *ws, size_t have, size_t need) {
   if (need == 0) return ZP_OK;
