@@ -37,6 +37,11 @@ WORKLOADS = {
     "longtail-128k-gqa32x8": dict(T=131072, Hq=32, Hkv=8, d=128, seed=1003, mix="longtail", C=4, bwd=True, remap=True),
     "lognormal-64k-mha32": dict(T=65536, Hq=32, Hkv=32, d=128, seed=1002, mix="lognormal", C=0, bwd=True, remap=False),
     "lognormal-256k-gqa64x8": dict(T=262144, Hq=64, Hkv=8, d=128, seed=1005, mix="lognormal", C=0, bwd=True, remap=True),
+    # forward of what ONE device of an 8-device node computes after the hierarchical partitioner has placed the
+    # 128K long-tail batch (capacity 20480 tokens per device): its local sequences whole, and for every ring
+    # sequence the Q chunks of its ring rank against their causal KV chunks, merged by LSE
+    "rankshare-p8-longtail-128k": dict(T=131072, Hq=32, Hkv=8, d=128, seed=1003, mix="longtail", C=0, bwd=False,
+                                       remap=False, rank_share=dict(P=8, N=1, L=20480, device=0)),
 }
 
 
@@ -56,6 +61,14 @@ class Job:
         else:
             lin_lengths = synth.lengths_lognormal(T, w["seed"])
         self.lin_lengths = lin_lengths
+        self.share = None
+        if w.get("rank_share"):
+            rs = w["rank_share"]
+            placements, _, _ = B.partition(lin_lengths, rs["P"], rs["N"], rs["L"])
+            mine = [pl for pl in placements if pl["node"] == 0 and pl["device"] == rs["device"]]
+            self.share = mine
+            lin_lengths = [lin_lengths[pl["seq"]] for pl in mine]   # ring sequences are resident in full (their KV)
+            T = w["T"] = int(sum(lin_lengths))
         if w["remap"]:
             idx, attn_lengths, order = synth.balanced_attention_layout(lin_lengths, R=8)
         else:
@@ -83,6 +96,15 @@ class Job:
                     self.skip[s] = 1
                     p, m, r = B.chunk_pairs(int(self.cu[s]), L, w["C"], row0=rows)
                     pairs += list(p); merges += list(m); rows += r
+        share_pairs = 0
+        if self.share:
+            for s, pl in enumerate(self.share):
+                if pl["ring"] > 1:
+                    self.skip[s] = 1
+                    p, m, r = B.chunk_pairs(int(self.cu[s]), attn_lengths[s], 2 * pl["ring"], rank=pl["rank"], row0=rows)
+                    pairs += list(p); merges += list(m); rows += r
+                    for x in p:   # causal (query, key) pairs this rank computes
+                        share_pairs += sum(max(0, min(x.k_len, x.q_pos0 + i - x.k_pos0 + 1)) for i in range(x.q_len))
         self.n_long = int(self.skip.sum())
         self.pairs = (B.ZpPair * len(pairs))(*pairs) if pairs else None
         self.n_pairs = len(pairs)
@@ -94,6 +116,9 @@ class Job:
             self.lse_part = torch.empty((Hq, rows), dtype=torch.float32, device=dev)
         self.pairs_total = pairs_of(attn_lengths)
         self.pairs_long = pairs_of([L for L, s in zip(attn_lengths, self.skip) if s])
+        if self.share:
+            self.pairs_total = pairs_of([L for L, s in zip(attn_lengths, self.skip) if not s]) + share_pairs
+            self.pairs_long = share_pairs
         self.flops_fwd = 4 * d * Hq * self.pairs_total
         self.flops_bwd = 10 * d * Hq * self.pairs_total if w["bwd"] else 0
         self.merge_bytes = sum(m.len * Hq * (m.n_parts * (4 * d + 4) + 2 * d + 4) for m in merges)
@@ -176,6 +201,8 @@ def main():
     ap.add_argument("--workload", default="longtail-128k-gqa32x8", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     a = ap.parse_args()
+    if WORKLOADS[a.workload].get("rank_share") or not WORKLOADS[a.workload]["bwd"]:
+        a.no_cpu_baseline = True   # the oracle sample is defined for the forward+backward workloads
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
         sys.exit(2)
@@ -222,8 +249,11 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": a.workload, "T": job.w["T"], "Hq": job.w["Hq"], "Hkv": job.w["Hkv"], "head_dim": job.w["d"],
                    "n_sequences": len(job.lengths), "max_len": max(job.lengths), "n_long_chunked": job.n_long,
-                   "chunks": job.w["C"], "stages": "remap,fwd,chunk_partial,lse_merge,remap_inv,bwd,remap_inv"
-                   if job.w["remap"] else "fwd,bwd"},
+                   "chunks": job.w["C"], "stages": ",".join(
+                       (["remap"] if job.w["remap"] else []) + ["fwd"] + (["chunk_partial", "lse_merge"] if job.n_pairs else [])
+                       + (["remap_inv"] if job.w["remap"] else [])
+                       + ((["remap"] if job.w["remap"] else []) + ["bwd"] + (["remap_inv"] if job.w["remap"] else [])
+                          if job.w["bwd"] else []))},
         "frac_of_mfma_peak": value / MFMA_BF16_PEAK_TFLOPS,
         "roofline": roofline,
         "kernels": kern,

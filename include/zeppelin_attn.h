@@ -38,7 +38,7 @@ extern "C" {
 #define ZP_EWORKSPACE (-3)   /* ws is NULL, misaligned or smaller than zp_workspace_bytes() */
 #define ZP_EHIP (-4)         /* a HIP runtime call failed; zp_strerror(ZP_EHIP) carries its text */
 
-#define ZP_MAX_PARTS 8
+#define ZP_MAX_PARTS 16
 
 /* Problem shape. T packed tokens, S sequences, Hq query heads, Hkv key/value heads, head dim d.
  * scale multiplies q.k before the softmax; 0 selects 1/sqrt(d). */
@@ -127,6 +127,25 @@ int remap_tokens(const void *src, void *dst, int64_t row_bytes, const int32_t *i
  * *n_merges and *rows_used (partial rows consumed). Negative on error. */
 int zp_chunk_pairs(int32_t tok0, int32_t L, int32_t C, int32_t rank, int32_t row0, zp_pair *pairs, int32_t max_pairs,
                    zp_merge *merges, int32_t max_merges, int32_t *n_merges, int64_t *rows_used);
+
+/* One item of a device's work after partitioning: sequence `seq` runs on node `node`, device `device`, either
+ * whole (zone 0, ring 1) or as ring rank `rank` of a ring of `ring` devices (zone 1: intra-node, zone 2:
+ * inter-node), holding chunks `rank` and 2*ring-1-rank of 2*ring equal-length chunks; `tokens` of it live there. */
+typedef struct {
+  int32_t seq, zone, ring, rank, node, device, tokens;
+} zp_placement;
+
+/* Host-only: hierarchical sequence partitioner (Sec. 3.1, Alg. 1 inter-node then Alg. 2 intra-node) for S sequences
+ * of the given lengths on N nodes of P devices with token capacity L per device. Sequences at or above the
+ * inter-node threshold s1 (initially P*L, lowered until the rest fits node by node) are split evenly over
+ * ceil(|s| / s_avg) of the least loaded nodes and over all P devices of each; inside a node, sequences at or above
+ * s0 (initially L, lowered until the rest fits device by device) are split over ceil(|s|^2 / c_avg) <= P devices
+ * assigned round-robin (c_avg = sum |s|^2 / P); the rest go whole to the least loaded device. A sequence on a ring of
+ * G devices is cut into 2G equal-length chunks and rank r holds chunks r and 2G-1-r (Sec. 3.2).
+ * Writes up to max_out placements (node-major), the count to *n_out, the final s1 to *s1_final and the final s0 of
+ * every node to s0_final[N] (both optional). Returns ZP_EWORKSPACE if max_out was too small (*n_out = needed). */
+int zp_partition(const int32_t *lengths, int32_t S, int32_t P, int32_t N, int32_t L, zp_placement *out,
+                 int32_t max_out, int32_t *n_out, int32_t *s1_final, int32_t *s0_final);
 
 /* Measurement aid: per-kernel durations from hipEvents recorded on the launch stream.
  * zp_profile_enable(1) clears the records and starts recording every kernel the library launches (one

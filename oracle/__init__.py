@@ -21,7 +21,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "zeppelin_oracle.c")
 _LIB = os.path.join(_HERE, "libzeppelin_oracle.so")
-MAX_PARTS = 8
+MAX_PARTS = 16
 
 
 def build(force: bool = False) -> str:

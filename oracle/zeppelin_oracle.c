@@ -145,7 +145,7 @@ int zo_chunk_attn_partial(const double *q, const double *k, const double *v, int
   return 0;
 }
 
-#define ZO_MAX_PARTS 8
+#define ZO_MAX_PARTS 16
 /* One run of `len` output tokens starting at out_tok0, each the combination of n_parts partial rows:
  * part p contributes rows part_row0[p] .. part_row0[p]+len-1 of o_part / lse_part. */
 typedef struct {

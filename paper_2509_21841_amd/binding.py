@@ -14,7 +14,7 @@ import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libzeppelin_attn.so")
-MAX_PARTS = 8
+MAX_PARTS = 16
 FN_FWD, FN_BWD, FN_PARTIAL, FN_MERGE = 0, 1, 2, 3
 
 
@@ -30,6 +30,10 @@ class ZpPair(ctypes.Structure):
 class ZpMerge(ctypes.Structure):
     _fields_ = [("out_tok0", ctypes.c_int32), ("len", ctypes.c_int32), ("n_parts", ctypes.c_int32),
                 ("part_row0", ctypes.c_int32 * MAX_PARTS)]
+
+
+class ZpPlacement(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("seq", "zone", "ring", "rank", "node", "device", "tokens")]
 
 
 class ZpError(RuntimeError):
@@ -67,6 +71,9 @@ def lib() -> ctypes.CDLL:
     L.lse_merge.argtypes = [vp, vp, i64, ctypes.POINTER(ZpMerge), i32, vp, i64, vp, ctypes.POINTER(ZpShape), vp, sz, vp]
     L.remap_tokens.restype = ctypes.c_int
     L.remap_tokens.argtypes = [vp, vp, i64, vp, i64, i32, vp]
+    L.zp_partition.restype = ctypes.c_int
+    L.zp_partition.argtypes = [vp, i32, i32, i32, i32, ctypes.POINTER(ZpPlacement), i32, ctypes.POINTER(i32),
+                               ctypes.POINTER(i32), vp]
     L.zp_profile_enable.restype = ctypes.c_int
     L.zp_profile_enable.argtypes = [ctypes.c_int]
     L.zp_profile_count.restype = ctypes.c_int
@@ -263,3 +270,17 @@ def profile_records():
         _check(lib().zp_profile_get(i, buf, 64, ctypes.byref(ms)))
         out.append((buf.value.decode(), float(ms.value)))
     return out
+
+
+def partition(lengths, P: int, N: int, L: int):
+    """Host helper: hierarchical partitioner -> (placements as dicts, s1, [s0 per node])."""
+    lens = np.ascontiguousarray(lengths, dtype=np.int32)
+    cap = max(len(lens) * max(P, 1) * max(N, 1), 1)
+    out = (ZpPlacement * cap)()
+    n = ctypes.c_int32(0)
+    s1 = ctypes.c_int32(0)
+    s0 = np.zeros(N, np.int32)
+    _check(lib().zp_partition(lens.ctypes.data_as(ctypes.c_void_p), len(lens), int(P), int(N), int(L), out, cap,
+                              ctypes.byref(n), ctypes.byref(s1), s0.ctypes.data_as(ctypes.c_void_p)))
+    pl = [{f: getattr(out[i], f) for f, _ in ZpPlacement._fields_} for i in range(n.value)]
+    return pl, int(s1.value), [int(x) for x in s0]

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libzeppelin_attn.so")
-SOURCES = ["zp_api.hip", "attn_fwd.hip", "attn_bwd.hip", "lse_merge.hip", "remap.hip"]
+SOURCES = ["zp_api.hip", "attn_fwd.hip", "attn_bwd.hip", "lse_merge.hip", "remap.hip", "zp_partition.cpp"]
 # packed-fp32 VALU forms are switched off on purpose for this target
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument",
@@ -35,7 +35,7 @@ def build(verbose: bool = False) -> str:
     hipcc = _hipcc()
 
     def compile_one(src):
-        obj = os.path.join(objdir, src.replace(".hip", ".o"))
+        obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
         r = subprocess.run([hipcc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj], capture_output=True, text=True)
         msg = _filter(r.stdout + r.stderr)
         if r.returncode != 0:

@@ -4,7 +4,7 @@
 // n_parts partial LSEs (broadcast within the row) and n_parts float4, writes 4 bf16.
 #include "zp_common.h"
 
-#define ZP_MAX_PARTS 8
+#define ZP_MAX_PARTS 16
 struct zp_merge_dev {
   int32_t out_tok0, len, n_parts;
   int32_t part_row0[ZP_MAX_PARTS];

@@ -1,0 +1,154 @@
+// Host-side hierarchical sequence partitioner (Sec. 3.1, Alg. 1 and Alg. 2): decides, from the lengths of a global
+// batch, which sequences a device runs whole (local zone) and which it shares on a ring (intra-node / inter-node
+// zone), i.e. what the attention engine's work list on each device is made of. Pure integer host code.
+#include <algorithm>
+#include <cstdint>
+#include <numeric>
+#include <vector>
+
+#include "../../include/zeppelin_attn.h"
+
+namespace {
+
+struct NodeItem {
+  int32_t seq;
+  int32_t k;  // number of nodes the sequence spans (0: whole sequence placed in this node)
+  int32_t m;  // index of this node among them
+};
+
+inline int64_t chunk_bound(int64_t len, int64_t c, int64_t G) { return (c * len) / (2 * G); }
+// tokens ring rank r of G holds: chunks r and 2G-1-r of 2G equal-length chunks (Sec. 3.2)
+inline int32_t ring_share(int64_t len, int64_t G, int64_t r) {
+  return (int32_t)((chunk_bound(len, r + 1, G) - chunk_bound(len, r, G)) +
+                   (chunk_bound(len, 2 * G - r, G) - chunk_bound(len, 2 * G - 1 - r, G)));
+}
+inline int64_t ceil_div_frac(double num, double den) {
+  double q = num / den;
+  int64_t f = (int64_t)q;
+  return (double)f < q ? f + 1 : f;
+}
+template <class Load>
+int argmin_load(const Load &load) {
+  int best = 0;
+  for (int i = 1; i < (int)load.size(); i++)
+    if (load[i] < load[best]) best = i;
+  return best;
+}
+
+}  // namespace
+
+extern "C" int zp_partition(const int32_t *lengths, int32_t S, int32_t P, int32_t N, int32_t L, zp_placement *out,
+                            int32_t max_out, int32_t *n_out, int32_t *s1_final, int32_t *s0_final) {
+  if (!lengths || S < 0 || P < 1 || N < 1 || L < 1 || !out || !n_out) return ZP_EINVAL;
+  for (int s = 0; s < S; s++)
+    if (lengths[s] < 0) return ZP_EINVAL;
+  std::vector<int32_t> order(S);
+  std::iota(order.begin(), order.end(), 0);
+  std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return lengths[a] > lengths[b]; });
+
+  // ---- Alg. 1: inter-node partitioning. Lower the threshold s1 until every shorter sequence fits a node.
+  const int64_t node_cap = (int64_t)P * L;
+  int64_t s1 = node_cap;
+  std::vector<std::vector<NodeItem>> node_items;
+  for (;;) {
+    node_items.assign(N, {});
+    std::vector<int64_t> load(N, 0);
+    // order is descending, so z2 is a prefix
+    int split = 0;
+    while (split < S && lengths[order[split]] >= s1) split++;
+    if (split > 0) {
+      int64_t total = 0;
+      for (int i = 0; i < split; i++) total += lengths[order[i]];
+      const double s_avg = (double)total / N;
+      for (int i = 0; i < split; i++) {
+        const int32_t s = order[i];
+        const int32_t k = (int32_t)std::min<int64_t>(N, ceil_div_frac((double)lengths[s], s_avg));
+        std::vector<int> idx(N);
+        std::iota(idx.begin(), idx.end(), 0);
+        std::stable_sort(idx.begin(), idx.end(), [&](int a, int b) { return load[a] < load[b]; });
+        idx.resize(k);
+        std::sort(idx.begin(), idx.end());
+        for (int m = 0; m < k; m++) {
+          node_items[idx[m]].push_back({s, k, m});
+          for (int p = 0; p < P; p++) load[idx[m]] += ring_share(lengths[s], (int64_t)k * P, (int64_t)m * P + p);
+        }
+      }
+    }
+    bool again = false;
+    for (int i = split; i < S; i++) {
+      const int32_t s = order[i];
+      const int n = argmin_load(load);
+      if (lengths[s] + load[n] > node_cap) {
+        s1 = lengths[order[split]];  // the longest sequence still below the threshold joins the inter-node zone
+        again = true;
+        break;
+      }
+      node_items[n].push_back({s, 0, 0});
+      load[n] += lengths[s];
+    }
+    if (!again) break;
+  }
+  if (s1_final) *s1_final = (int32_t)std::min<int64_t>(s1, INT32_MAX);
+
+  // ---- Alg. 2: intra-node partitioning, node by node.
+  int32_t n_written = 0;
+  auto emit = [&](int32_t seq, int32_t zone, int32_t ring, int32_t rank, int32_t node, int32_t dev, int32_t tokens) {
+    if (n_written < max_out) out[n_written] = zp_placement{seq, zone, ring, rank, node, dev, tokens};
+    n_written++;
+  };
+  for (int n = 0; n < N; n++) {
+    std::vector<int32_t> whole;  // descending length (node_items keeps the global order)
+    for (const NodeItem &it : node_items[n])
+      if (it.k == 0) whole.push_back(it.seq);
+    int64_t s0 = L;
+    std::vector<zp_placement> tmp;
+    for (;;) {
+      tmp.clear();
+      std::vector<int64_t> load(P, 0);
+      for (const NodeItem &it : node_items[n]) {
+        if (it.k == 0) continue;
+        const int64_t G = (int64_t)it.k * P;
+        for (int p = 0; p < P; p++) {
+          const int32_t t = ring_share(lengths[it.seq], G, (int64_t)it.m * P + p);
+          tmp.push_back(zp_placement{it.seq, 2, (int32_t)G, (int32_t)(it.m * P + p), n, p, t});
+          load[p] += t;
+        }
+      }
+      int split = 0;  // whole[0 .. split) is z1 (length >= s0), the rest z0
+      while (split < (int)whole.size() && lengths[whole[split]] >= s0) split++;
+      if (split > 0) {
+        double c_sum = 0;
+        for (int i = 0; i < split; i++) c_sum += (double)lengths[whole[i]] * lengths[whole[i]];
+        const double c_avg = c_sum / P;
+        int64_t next_slot = 0;
+        for (int i = 0; i < split; i++) {
+          const int32_t s = whole[i];
+          const int64_t G = std::min<int64_t>(P, ceil_div_frac((double)lengths[s] * lengths[s], c_avg));
+          for (int64_t r = 0; r < G; r++) {
+            const int p = (int)(next_slot++ % P);
+            const int32_t t = G > 1 ? ring_share(lengths[s], G, r) : lengths[s];
+            tmp.push_back(zp_placement{s, 1, (int32_t)G, (int32_t)r, n, p, t});
+            load[p] += t;
+          }
+        }
+      }
+      bool again = false;
+      for (int i = split; i < (int)whole.size(); i++) {
+        const int32_t s = whole[i];
+        const int p = argmin_load(load);
+        if (lengths[s] + load[p] > L) {
+          s0 = lengths[whole[split]];
+          again = true;
+          break;
+        }
+        tmp.push_back(zp_placement{s, 0, 1, 0, n, p, lengths[s]});
+        load[p] += lengths[s];
+      }
+      if (!again) break;
+    }
+    if (s0_final) s0_final[n] = (int32_t)s0;
+    for (const zp_placement &pl : tmp) emit(pl.seq, pl.zone, pl.ring, pl.rank, pl.node, pl.device, pl.tokens);
+  }
+  *n_out = n_written;
+  return n_written > max_out ? ZP_EWORKSPACE : ZP_OK;
+}

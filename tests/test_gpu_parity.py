@@ -46,7 +46,7 @@ def test_remap_empty_and_layout_round_trip():
 
 
 # ---- merge -------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("Hq,d,n,parts", [(4, 64, 37, 3), (32, 128, 300, 4), (2, 128, 9, 1), (3, 64, 20, 8)])
+@pytest.mark.parametrize("Hq,d,n,parts", [(4, 64, 37, 3), (32, 128, 300, 4), (2, 128, 9, 1), (3, 64, 20, 8), (2, 128, 11, 16)])
 def test_lse_merge_matches_oracle(Hq, d, n, parts):
     g = torch.Generator(device="cpu"); g.manual_seed(Hq * 1000 + n)
     rows = parts * n + 5

@@ -69,7 +69,7 @@ def test_remap_and_merge_validation_without_device():
     m = (B.ZpMerge * 1)()
     m[0].out_tok0, m[0].len, m[0].n_parts = 90, 20, 1                            # runs past T
     assert L.lse_merge(1 << 12, 1 << 12, 100, m, 1, 1 << 12, 256, 1 << 12, ctypes.byref(sh), 1 << 12, 1 << 20, None) == -1
-    m[0].out_tok0, m[0].len, m[0].n_parts = 0, 20, 9                             # too many parts
+    m[0].out_tok0, m[0].len, m[0].n_parts = 0, 20, 17                            # too many parts
     assert L.lse_merge(1 << 12, 1 << 12, 100, m, 1, 1 << 12, 256, 1 << 12, ctypes.byref(sh), 1 << 12, 1 << 20, None) == -1
     p = (B.ZpPair * 1)()
     p[0].q_tok0, p[0].q_len, p[0].k_tok0, p[0].k_len, p[0].out_row0 = 0, 50, 60, 50, 0   # keys past T

@@ -1,0 +1,110 @@
+"""Hierarchical partitioner (Sec. 3.1): the step-by-step oracle against hand-worked examples and the properties
+the paper states, and the library's host implementation against the oracle (CPU only)."""
+import collections
+import os
+
+import numpy as np
+import pytest
+
+from oracle import partitioner as opt
+from paper_2509_21841_amd import binding as B
+from paper_2509_21841_amd import synth
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+KEYS = ("seq", "zone", "ring", "rank", "node", "device", "tokens")
+
+
+def golden_cases():
+    cases, cur = [], None
+    for line in open(os.path.join(HERE, "golden", "partition_examples.txt")):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        tok = line.split()
+        if tok[0] == "case":
+            cur = dict(name=tok[1], P=int(tok[2]), N=int(tok[3]), L=int(tok[4]), lengths=[int(x) for x in tok[5:]], rows=[])
+            cases.append(cur)
+        elif tok[0] == "thresholds":
+            cur["s1"], cur["s0"] = int(tok[1]), [int(x) for x in tok[2:]]
+        else:
+            cur["rows"].append(dict(zip(KEYS, map(int, tok))))
+    return cases
+
+
+def canon(pl):
+    return sorted(tuple(p[k] for k in KEYS) for p in pl)
+
+
+@pytest.mark.parametrize("case", golden_cases(), ids=lambda c: c["name"])
+def test_oracle_and_library_match_hand_worked_examples(case):
+    for impl in (opt.partition, B.partition):
+        pl, s1, s0 = impl(case["lengths"], case["P"], case["N"], case["L"])
+        assert canon(pl) == canon(case["rows"]) and s1 == case["s1"] and s0 == case["s0"]
+
+
+def check_properties(lengths, P, N, L, pl, s1, s0):
+    by_seq = collections.defaultdict(list)
+    for p in pl:
+        by_seq[p["seq"]].append(p)
+    assert sorted(by_seq) == [s for s in range(len(lengths))]                      # every sequence placed
+    assert sum(p["tokens"] for p in pl) == sum(lengths)                            # token conservation
+    load = collections.Counter(); has_local = set()
+    for s, items in by_seq.items():
+        zone = items[0]["zone"]; G = items[0]["ring"]
+        assert all(i["zone"] == zone and i["ring"] == G for i in items)
+        assert sorted(i["rank"] for i in items) == list(range(G))                  # every ring rank exactly once
+        assert sum(i["tokens"] for i in items) == lengths[s]
+        if zone == 2:
+            assert lengths[s] >= s1 and G % P == 0                                 # spans whole nodes
+        elif zone == 1:
+            assert s0[items[0]["node"]] <= lengths[s] < s1 and len({i["node"] for i in items}) == 1 and G <= P
+        else:
+            assert lengths[s] < s0[items[0]["node"]] and G == 1
+        for i in items:
+            load[(i["node"], i["device"])] += i["tokens"]
+            if zone == 0:
+                has_local.add((i["node"], i["device"]))
+            # a ring rank holds chunks r and 2G-1-r of 2G equal-length chunks (Sec. 3.2)
+            if G > 1:
+                assert i["tokens"] == opt.ring_tokens(lengths[s], G, i["rank"])
+    for dev in has_local:                                                          # greedy step never overfills
+        assert load[dev] <= L
+    return load
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_properties_and_library_equals_oracle_on_random_batches(seed):
+    r = np.random.default_rng(seed)
+    P, N = int(r.choice([1, 2, 4, 8])), int(r.choice([1, 2, 4]))
+    S = int(r.integers(1, 60))
+    lengths = np.clip(np.rint(np.exp(r.normal(6.5, 1.3, S))), 1, 200000).astype(int).tolist()
+    slack = float(r.choice([1.0, 1.1, 1.5, 3.0]))
+    L = max(1, int(np.ceil(sum(lengths) * slack / (P * N))))
+    pl, s1, s0 = opt.partition(lengths, P, N, L)
+    check_properties(lengths, P, N, L, pl, s1, s0)
+    pl2, s1b, s0b = B.partition(lengths, P, N, L)
+    assert canon(pl2) == canon(pl) and s1b == s1 and s0b == s0
+
+
+def test_degenerate_cases():
+    # everything short and roomy: all local, balanced within one sequence length
+    lengths = [100] * 64
+    pl, s1, s0 = opt.partition(lengths, 8, 1, 1000)
+    load = check_properties(lengths, 8, 1, 1000, pl, s1, s0)
+    assert all(p["zone"] == 0 for p in pl) and set(load.values()) == {800}
+    # one sequence larger than a node: a ring over every device of every node it needs
+    lengths = [64000, 10, 10]
+    pl, s1, s0 = opt.partition(lengths, 4, 2, 8000)
+    big = [p for p in pl if p["seq"] == 0]
+    assert big[0]["zone"] == 2 and big[0]["ring"] == 8 and len(big) == 8 and all(p["tokens"] == 8000 for p in big)
+    assert canon(B.partition(lengths, 4, 2, 8000)[0]) == canon(pl)
+    # empty batch
+    assert opt.partition([], 2, 2, 10)[0] == [] and B.partition([], 2, 2, 10)[0] == []
+
+
+def test_paper_sized_batches():
+    for lengths, P, N, L in ((synth.lengths_lognormal(262144, 1005), 8, 4, 10240),
+                             (synth.lengths_longtail(131072, 1003)[0], 8, 2, 10240)):
+        pl, s1, s0 = opt.partition(lengths, P, N, L)
+        check_properties(lengths, P, N, L, pl, s1, s0)
+        assert canon(B.partition(lengths, P, N, L)[0]) == canon(pl)
