@@ -64,10 +64,10 @@ typedef struct {
 } zp_merge;
 
 /* Which entry point a workspace query is for. */
-enum { ZP_FN_FWD = 0, ZP_FN_BWD = 1, ZP_FN_PARTIAL = 2, ZP_FN_MERGE = 3 };
+enum { ZP_FN_FWD = 0, ZP_FN_BWD = 1, ZP_FN_PARTIAL = 2, ZP_FN_MERGE = 3, ZP_FN_PARTIAL_BWD = 4 };
 
-/* Bytes of `ws` an entry point needs. n_desc: number of pairs (ZP_FN_PARTIAL) or merges (ZP_FN_MERGE),
- * ignored otherwise. cu_seqlens_host may be NULL for ZP_FN_PARTIAL / ZP_FN_MERGE. Returns 0 on bad input. */
+/* Bytes of `ws` an entry point needs. n_desc: number of pairs (ZP_FN_PARTIAL, ZP_FN_PARTIAL_BWD) or merges (ZP_FN_MERGE),
+ * ignored otherwise. cu_seqlens_host may be NULL for ZP_FN_PARTIAL / ZP_FN_MERGE / ZP_FN_PARTIAL_BWD. Returns 0 on bad input. */
 size_t zp_workspace_bytes(int which_fn, const zp_shape *sh, const int32_t *cu_seqlens_host, int64_t n_desc);
 
 /* Causal softmax attention of every sequence of the packed batch (Sec. 3.2, local sequences; Sec. 2.1):
@@ -103,6 +103,23 @@ int varlen_attn_bwd(const void *dout, const void *q, const void *k, const void *
 int chunk_attn_partial(const void *q, const void *k, const void *v, int64_t q_stride, int64_t k_stride,
                        int64_t v_stride, const zp_pair *pairs_host, int32_t n_pairs, float *o_part, float *lse_part,
                        int64_t part_rows, const zp_shape *sh, void *ws, size_t ws_bytes, void *stream);
+
+/* Backward of one ring round of chunk pairs (Sec. 3.2 rounds, Sec. 5.4: the backward runs them in reverse): for
+ * every pair and head, with P_ij = exp(scale q_i.k_j - LSE_i) over the pair's causally visible (i, j), LSE the
+ * MERGED log-sum-exp of the whole row and D_i = dO_i.O_i from the merged O,
+ *   dq_acc[i] += scale sum_j dS_ij k_j ;  dk_acc[j] += scale sum_{h in group} sum_i dS_ij q_i ;
+ *   dv_acc[j] += sum_{h in group} sum_i P_ij dO_i ,   dS_ij = P_ij (dO_i.v_j - D_i).
+ * dq_acc [T][Hq][d], dk_acc / dv_acc [T][Hkv][d] are device float accumulators the results are ADDED to (the caller
+ * zeroes them before the first round); summed over all causal pairs of a sequence they equal varlen_attn_bwd's
+ * result. Within one call the Q row ranges of the pairs must be pairwise disjoint and so must the KV row ranges
+ * (checked; ZP_EINVAL): that is one ring round, and rounds are ordered by the stream. */
+int chunk_attn_partial_bwd(const void *dout, const void *q, const void *k, const void *v, const void *o,
+                           const float *lse, int64_t do_stride, int64_t q_stride, int64_t k_stride, int64_t v_stride,
+                           int64_t o_stride, const zp_pair *pairs_host, int32_t n_pairs, float *dq_acc, float *dk_acc,
+                           float *dv_acc, const zp_shape *sh, void *ws, size_t ws_bytes, void *stream);
+
+/* Rounds n float accumulator values to bfloat16 (n % 8 == 0; src, dst 16-byte aligned device pointers). */
+int zp_accum_to_bf16(const float *src, void *dst, int64_t n, void *stream);
 
 /* Online-softmax combination of partial results (Sec. 3.2, "standard ring attention pattern"):
  *   LSE = log sum_p exp(LSE_p),  O = sum_p exp(LSE_p - LSE) O_p ; parts with LSE_p = -inf weigh 0 and a

@@ -145,6 +145,47 @@ def chunk_attn_partial(q, k, v, pairs, part_rows, scale=None):
     return o_part, lse_part
 
 
+def chunk_attn_partial_bwd(dout, q, k, v, pairs, lse, D, dq, dk, dv, scale=None):
+    """Adds the pairs' backward contributions to dq [T,Hq,d], dk, dv [T,Hkv,d] (float64, modified in place and
+    returned). lse, D: [Hq,T] statistics of the whole rows (D = sum_c dO*O)."""
+    dout, dop = _f64(dout); q, qp = _f64(q); k, kp = _f64(k); v, vp = _f64(v)
+    lse, lp = _f64(lse); D, Dp = _f64(D)
+    T, Hq, d = q.shape
+    Hkv = k.shape[1]
+    scale = default_scale(d) if scale is None else float(scale)
+    arr = (_Pair * max(len(pairs), 1))()
+    for n, p in enumerate(pairs):
+        vals = [p[f] if isinstance(p, dict) else getattr(p, f) for f, _ in _Pair._fields_]
+        for (f, _), val in zip(_Pair._fields_, vals):
+            setattr(arr[n], f, int(val))
+    for a in (dq, dk, dv):
+        assert a.dtype == np.float64 and a.flags.c_contiguous
+    rc = _L().zo_chunk_attn_partial_bwd(dop, qp, kp, vp, ctypes.c_int64(T), Hq, Hkv, d, arr, len(pairs),
+                                        ctypes.c_double(scale), lp, Dp, dq.ctypes.data_as(ctypes.c_void_p),
+                                        dk.ctypes.data_as(ctypes.c_void_p), dv.ctypes.data_as(ctypes.c_void_p))
+    if rc:
+        raise ValueError("oracle: invalid argument")
+    return dq, dk, dv
+
+
+def f32_to_bf16_bits(x):
+    """bfloat16 bit patterns (uint16) of float32 values, round to nearest, ties to even; NaN stays NaN (quiet)."""
+    u = np.ascontiguousarray(x, np.float32).view(np.uint32).astype(np.uint64)
+    keep = u >> 16
+    rem = u & 0xFFFF
+    up = (rem > 0x8000) | ((rem == 0x8000) & ((keep & 1) == 1))
+    out = (keep + up).astype(np.uint32)
+    nan = np.isnan(np.ascontiguousarray(x, np.float32))
+    out = np.where(nan, (u >> 16) | 0x40, out)
+    return out.astype(np.uint16)
+
+
+def ring_rounds(C: int):
+    """Causal chunk pairs grouped into rounds in which every Q chunk and every KV chunk appears at most once:
+    round t holds the pairs (qc, qc - t)."""
+    return [[(qc, qc - t) for qc in range(t, C)] for t in range(C)]
+
+
 def lse_merge(o_part, lse_part, merges, T, o=None, lse=None):
     """merges: list of (out_tok0, len, [part_row0...]). Rows outside every merge keep o/lse as passed
     (NaN when not passed). -> (o [T,Hq,d], lse [Hq,T])."""

@@ -337,6 +337,46 @@ int zo_varlen_attn_bwd_sample(const double *dout, const double *q, const double 
   return 0;
 }
 
+/* Backward contribution of (Q chunk, KV chunk) pairs, ADDED to dq/dk/dv: the sums of the whole-sequence backward
+ * restricted to the pair's causally visible (i, j). lse [Hq][T] and D [Hq][T] are the statistics of the WHOLE rows
+ * (merged over all KV chunks): what a ring rank holds after the forward rounds (Sec. 3.2, Sec. 5.4). */
+int zo_chunk_attn_partial_bwd(const double *dout, const double *q, const double *k, const double *v, int64_t T,
+                              int Hq, int Hkv, int d, const zo_pair *pairs, int n_pairs, double scale,
+                              const double *lse, const double *D, double *dq, double *dk, double *dv) {
+  if (!dout || !q || !k || !v || !lse || !D || !dq || !dk || !dv || Hq <= 0 || Hkv <= 0 || d <= 0 || Hq % Hkv) return -1;
+  const int grp = Hq / Hkv;
+  for (int p = 0; p < n_pairs; p++) {
+    const zo_pair *pr = &pairs[p];
+    if (pr->q_len < 0 || pr->k_len < 0 || pr->q_tok0 < 0 || pr->k_tok0 < 0 || pr->q_tok0 + (int64_t)pr->q_len > T ||
+        pr->k_tok0 + (int64_t)pr->k_len > T)
+      return -1;
+  }
+  for (int p = 0; p < n_pairs; p++) {
+    const zo_pair *pr = &pairs[p];
+    for (int h = 0; h < Hq; h++) {
+      const int g = h / grp;
+      for (int ii = 0; ii < pr->q_len; ii++) {
+        const int64_t ti = (int64_t)pr->q_tok0 + ii;
+        const double *qi = q + (ti * Hq + h) * d, *doi = dout + (ti * Hq + h) * d;
+        const double lse_i = lse[(int64_t)h * T + ti], D_i = D[(int64_t)h * T + ti];
+        for (int jj = 0; jj < pr->k_len; jj++) {
+          if ((int64_t)pr->k_pos0 + jj > (int64_t)pr->q_pos0 + ii) break; /* not visible */
+          const int64_t tj = (int64_t)pr->k_tok0 + jj;
+          const double *kj = k + (tj * Hkv + g) * d, *vj = v + (tj * Hkv + g) * d;
+          const double pij = exp(scale * dotd(qi, kj, d) - lse_i);
+          const double ds = pij * (dotd(doi, vj, d) - D_i);
+          for (int c = 0; c < d; c++) {
+            dq[(ti * Hq + h) * d + c] += scale * ds * kj[c];
+            dk[(tj * Hkv + g) * d + c] += scale * ds * qi[c];
+            dv[(tj * Hkv + g) * d + c] += pij * doi[c];
+          }
+        }
+      }
+    }
+  }
+  return 0;
+}
+
 /* Token move of the remapping layer: mode 0 gathers dst[i] = src[idx[i]], mode 1 scatters
  * dst[idx[i]] = src[i]; rows are raw bytes. */
 int zo_remap_tokens(const void *src, void *dst, int64_t row_bytes, const int32_t *idx, int64_t n_rows, int mode) {

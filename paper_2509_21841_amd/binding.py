@@ -15,7 +15,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libzeppelin_attn.so")
 MAX_PARTS = 16
-FN_FWD, FN_BWD, FN_PARTIAL, FN_MERGE = 0, 1, 2, 3
+FN_FWD, FN_BWD, FN_PARTIAL, FN_MERGE, FN_PARTIAL_BWD = 0, 1, 2, 3, 4
 
 
 class ZpShape(ctypes.Structure):
@@ -67,6 +67,11 @@ def lib() -> ctypes.CDLL:
     L.chunk_attn_partial.restype = ctypes.c_int
     L.chunk_attn_partial.argtypes = [vp, vp, vp, i64, i64, i64, ctypes.POINTER(ZpPair), i32, vp, vp, i64,
                                      ctypes.POINTER(ZpShape), vp, sz, vp]
+    L.chunk_attn_partial_bwd.restype = ctypes.c_int
+    L.chunk_attn_partial_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, ctypes.POINTER(ZpPair), i32,
+                                         vp, vp, vp, ctypes.POINTER(ZpShape), vp, sz, vp]
+    L.zp_accum_to_bf16.restype = ctypes.c_int
+    L.zp_accum_to_bf16.argtypes = [vp, vp, i64, vp]
     L.lse_merge.restype = ctypes.c_int
     L.lse_merge.argtypes = [vp, vp, i64, ctypes.POINTER(ZpMerge), i32, vp, i64, vp, ctypes.POINTER(ZpShape), vp, sz, vp]
     L.remap_tokens.restype = ctypes.c_int
@@ -178,7 +183,10 @@ def _pairs_array(pairs):
         return pairs, len(pairs)
     arr = (ZpPair * max(len(pairs), 1))()
     for n, p in enumerate(pairs):
-        vals = [p[f] for f, _ in ZpPair._fields_] if isinstance(p, dict) else list(p)
+        if isinstance(p, ZpPair):
+            vals = [getattr(p, f) for f, _ in ZpPair._fields_]
+        else:
+            vals = [p[f] for f, _ in ZpPair._fields_] if isinstance(p, dict) else list(p)
         for (f, _), val in zip(ZpPair._fields_, vals):
             setattr(arr[n], f, int(val))
     return arr, len(pairs)
@@ -214,6 +222,45 @@ def chunk_attn_partial(q, k, v, pairs, part_rows, o_part=None, lse_part=None, sc
                                     arr, n, o_part.data_ptr(), lse_part.data_ptr(), int(part_rows), ctypes.byref(sh),
                                     ws.data_ptr(), ws.numel(), _stream_ptr(stream)))
     return o_part, lse_part
+
+
+def chunk_attn_partial_bwd(dout, q, k, v, o, lse, pairs, dq_acc, dk_acc, dv_acc, scale=0.0, ws=None, stream=None):
+    """One ring round of the chunked backward: ADDS the pairs' contributions to the float accumulators
+    dq_acc [T,Hq,d], dk_acc / dv_acc [T,Hkv,d] (contiguous). Q ranges and KV ranges of the pairs must be disjoint."""
+    T, Hq, d = q.shape
+    Hkv = k.shape[1]
+    sh = make_shape(T, 0, Hq, Hkv, d, scale)
+    arr, n = _pairs_array(pairs)
+    for a in (dq_acc, dk_acc, dv_acc):
+        assert a.dtype == torch.float32 and a.is_contiguous()
+    need = workspace_bytes(FN_PARTIAL_BWD, sh, None, n)
+    if ws is None:
+        ws = workspace(need, q.device, "partial_bwd")
+    _check(lib().chunk_attn_partial_bwd(dout.data_ptr(), q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(),
+                                        lse.data_ptr(), _tok_stride(dout), _tok_stride(q), _tok_stride(k), _tok_stride(v),
+                                        _tok_stride(o), arr, n, dq_acc.data_ptr(), dk_acc.data_ptr(), dv_acc.data_ptr(),
+                                        ctypes.byref(sh), ws.data_ptr(), ws.numel(), _stream_ptr(stream)))
+    return dq_acc, dk_acc, dv_acc
+
+
+def accum_to_bf16(src, dst=None, stream=None):
+    """Rounds a contiguous float32 accumulator tensor to bfloat16 on the device."""
+    assert src.dtype == torch.float32 and src.is_contiguous()
+    if dst is None:
+        dst = torch.empty(src.shape, dtype=torch.bfloat16, device=src.device)
+    _check(lib().zp_accum_to_bf16(src.data_ptr(), dst.data_ptr(), src.numel(), _stream_ptr(stream)))
+    return dst
+
+
+def ring_rounds(pairs, C: int):
+    """Groups the C(C+1)/2 causal pairs of zp_chunk_pairs (Q chunk major) into C rounds: round t = pairs (qc, qc - t)."""
+    by = {}
+    n = 0
+    for qc in range(C):
+        for kc in range(qc + 1):
+            by[(qc, kc)] = pairs[n]
+            n += 1
+    return [[by[(qc, qc - t)] for qc in range(t, C)] for t in range(C)]
 
 
 def lse_merge(o_part, lse_part, merges, o, lse, ws=None, stream=None):

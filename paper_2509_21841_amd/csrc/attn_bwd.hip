@@ -18,8 +18,9 @@ struct zp_bwd_params {
   const zp_tile *kv_tiles;
   int32_t n_dq_tiles, n_kv_tiles, Hq, Hkv, grp, T;
   float scale_log2, scale;
-  __bf16 *dq, *dk, *dv;
+  __bf16 *dq, *dk, *dv;      // outputs (bf16, overwritten) ...
   int64_t dq_stride, dkv_stride;
+  int32_t accumulate;        // ... or, when set, float accumulators of the same shapes that the results are ADDED to
 };
 
 namespace {
@@ -66,6 +67,20 @@ __device__ __forceinline__ void store_acc_rows(__bf16 *dst, const f32x16 (&acc)[
 #define ZP_SG_VALU 0x002
 #define ZP_SG_TRANS 0x400
 #define ZP_SG_DSREAD 0x100
+
+// accumulate variant of store_acc_rows: dst is float, the scaled accumulator is added to what is there
+template <int D>
+__device__ __forceinline__ void add_acc_rows(float *dst, const f32x16 (&acc)[D / 32], float mul) {
+#pragma unroll
+  for (int db = 0; db < D / 32; db++)
+#pragma unroll
+    for (int b = 0; b < 4; b++) {
+      f32x4 cur = *(const f32x4 *)(dst + db * 32 + b * 8);
+      cur[0] += acc[db][4 * b] * mul; cur[1] += acc[db][4 * b + 1] * mul;
+      cur[2] += acc[db][4 * b + 2] * mul; cur[3] += acc[db][4 * b + 3] * mul;
+      *(f32x4 *)(dst + db * 32 + b * 8) = cur;
+    }
+}
 
 // ------------------------------------------------------------------------------------------- dQ
 // One 32-key half of a K/V tile for one wave: S^T and dP^T chains, dS^T, then dQ^T += K^T dS^T.
@@ -214,7 +229,10 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
     __syncthreads();
   }
 
-  if (row_ok) store_acc_rows<D>(p.dq + tok * p.dq_stride + (int64_t)h * D + 4 * hi, dq_acc, p.scale);
+  if (row_ok) {
+    if (p.accumulate) add_acc_rows<D>((float *)p.dq + tok * p.dq_stride + (int64_t)h * D + 4 * hi, dq_acc, p.scale);
+    else store_acc_rows<D>(p.dq + tok * p.dq_stride + (int64_t)h * D + 4 * hi, dq_acc, p.scale);
+  }
 }
 
 // ------------------------------------------------------------------------------------------- dK, dV
@@ -431,8 +449,13 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
   }
 
   if (key_ok) {
-    store_acc_rows<D>(p.dk + ktok * p.dkv_stride + (int64_t)g * D + 4 * hi, dk_acc, p.scale);
-    store_acc_rows<D>(p.dv + ktok * p.dkv_stride + (int64_t)g * D + 4 * hi, dv_acc, 1.0f);
+    if (p.accumulate) {
+      add_acc_rows<D>((float *)p.dk + ktok * p.dkv_stride + (int64_t)g * D + 4 * hi, dk_acc, p.scale);
+      add_acc_rows<D>((float *)p.dv + ktok * p.dkv_stride + (int64_t)g * D + 4 * hi, dv_acc, 1.0f);
+    } else {
+      store_acc_rows<D>(p.dk + ktok * p.dkv_stride + (int64_t)g * D + 4 * hi, dk_acc, p.scale);
+      store_acc_rows<D>(p.dv + ktok * p.dkv_stride + (int64_t)g * D + 4 * hi, dv_acc, 1.0f);
+    }
   }
 }
 

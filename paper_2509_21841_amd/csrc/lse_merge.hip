@@ -4,6 +4,9 @@
 // n_parts partial LSEs (broadcast within the row) and n_parts float4, writes 4 bf16.
 #include "zp_common.h"
 
+extern "C" void zp_prof_begin(const char *name, hipStream_t stream);
+extern "C" void zp_prof_end(hipStream_t stream);
+
 #define ZP_MAX_PARTS 16
 struct zp_merge_dev {
   int32_t out_tok0, len, n_parts;
@@ -64,8 +67,29 @@ __global__ __launch_bounds__(MERGE_NT) void lse_merge_kernel(const float *__rest
 }
 }  // namespace
 
-extern "C" void zp_prof_begin(const char *name, hipStream_t stream);
-extern "C" void zp_prof_end(hipStream_t stream);
+
+namespace {
+// float accumulators -> bfloat16, 8 elements per lane
+__global__ __launch_bounds__(256) void accum_to_bf16_kernel(const float *__restrict__ src, __bf16 *__restrict__ dst, int64_t n8) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += (int64_t)gridDim.x * 256) {
+    const f32x4 a = __builtin_nontemporal_load((const f32x4 *)src + 2 * i);
+    const f32x4 b = __builtin_nontemporal_load((const f32x4 *)src + 2 * i + 1);
+    bf16x8 o = {(__bf16)a[0], (__bf16)a[1], (__bf16)a[2], (__bf16)a[3], (__bf16)b[0], (__bf16)b[1], (__bf16)b[2], (__bf16)b[3]};
+    *((bf16x8 *)dst + i) = o;
+  }
+}
+}  // namespace
+
+extern "C" int zp_launch_accum_to_bf16(const float *src, void *dst, int64_t n, hipStream_t stream) {
+  if (n == 0) return 0;
+  const int64_t n8 = n / 8;
+  int64_t grid = (n8 + 255) / 256;
+  if (grid > 256 * 64) grid = 256 * 64;
+  zp_prof_begin("accum_to_bf16", stream);
+  hipLaunchKernelGGL(accum_to_bf16_kernel, dim3((unsigned)grid), dim3(256), 0, stream, src, (__bf16 *)dst, n8);
+  zp_prof_end(stream);
+  return (int)hipGetLastError();
+}
 
 extern "C" int zp_merge_rows_per_item(void) { return MERGE_ROWS; }
 

@@ -34,7 +34,9 @@ struct zp_bwd_params {
   float scale_log2, scale;
   __bf16 *dq, *dk, *dv;
   int64_t dq_stride, dkv_stride;
+  int32_t accumulate;
 };
+int zp_launch_accum_to_bf16(const float *src, void *dst, int64_t n, hipStream_t stream);
 int zp_launch_attn_bwd(const zp_bwd_params *p, int d, hipStream_t stream);
 int zp_attn_bwd_block_rows(int d, int which);
 }
@@ -280,6 +282,11 @@ size_t zp_workspace_bytes(int which_fn, const zp_shape *sh, const int32_t *cu, i
       if (n_desc < 0) return 0;
       const int rpi = zp_merge_rows_per_item();
       return align256((size_t)n_desc * sizeof(zp_merge)) + align256(((size_t)sh->T / rpi + (size_t)n_desc + 1) * 8) + 256;
+    }
+    case ZP_FN_PARTIAL_BWD: {
+      if (n_desc < 0) return 0;
+      const size_t per_pair = (size_t)sh->T / zp_attn_bwd_block_rows(sh->d, 0) + (size_t)sh->T / zp_attn_bwd_block_rows(sh->d, 1) + 2;
+      return align256((size_t)n_desc * per_pair * sizeof(zp_tile)) + 2 * align256((size_t)sh->Hq * (size_t)sh->T * sizeof(float)) + 512;
     }
     case ZP_FN_BWD: {
       if (check_cu(cu, sh) != ZP_OK) return 0;
@@ -539,5 +546,104 @@ extern "C" int varlen_attn_bwd(const void *dout, const void *q, const void *k, c
   p.dq_stride = dq_stride; p.dkv_stride = dkv_stride;
   hipError_t e = (hipError_t)zp_launch_attn_bwd(&p, sh->d, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e, "attn_bwd launch");
+  return ZP_OK;
+}
+
+// Builds the dQ tiles (blocks of query rows of each pair's Q chunk against its KV chunk) and the dK/dV tiles (blocks
+// of key rows of each pair's KV chunk against the Q-chunk rows that can see them) of one ring round.
+static void plan_pairs_bwd(const zp_pair *pairs, int n_pairs, int bmq, int bnk, std::vector<CostTile> &qt,
+                           std::vector<CostTile> &kt) {
+  for (int i = 0; i < n_pairs; i++) {
+    const zp_pair &pr = pairs[i];
+    for (int32_t r0 = 0; r0 < pr.q_len; r0 += bmq) {
+      CostTile c;
+      c.t.q_tok0 = pr.q_tok0 + r0; c.t.q_rows = std::min(bmq, pr.q_len - r0); c.t.q_pos0 = pr.q_pos0 + r0;
+      c.t.k_tok0 = pr.k_tok0; c.t.k_len = pr.k_len; c.t.k_pos0 = pr.k_pos0;
+      c.t.out_row0 = c.t.q_tok0; c.t.aux = 0;
+      c.cost = tile_cost(c.t);
+      if (c.cost > 0) qt.push_back(c);
+    }
+    for (int32_t j0 = 0; j0 < pr.k_len; j0 += bnk) {
+      // first query row of the chunk that sees the block's first key
+      const int32_t off = std::max(0, pr.k_pos0 + j0 - pr.q_pos0);
+      if (off >= pr.q_len) continue;
+      CostTile c;
+      c.t.k_tok0 = pr.k_tok0 + j0; c.t.k_len = std::min(bnk, pr.k_len - j0); c.t.k_pos0 = pr.k_pos0 + j0;
+      c.t.q_tok0 = pr.q_tok0 + off; c.t.q_rows = pr.q_len - off; c.t.q_pos0 = pr.q_pos0 + off;
+      c.t.out_row0 = c.t.k_tok0; c.t.aux = 0;
+      c.cost = (c.t.q_rows + 63) / 64;
+      kt.push_back(c);
+    }
+  }
+  sort_by_cost(qt);
+  sort_by_cost(kt);
+}
+
+extern "C" int chunk_attn_partial_bwd(const void *dout, const void *q, const void *k, const void *v, const void *o,
+                                      const float *lse, int64_t do_stride, int64_t q_stride, int64_t k_stride,
+                                      int64_t v_stride, int64_t o_stride, const zp_pair *pairs, int32_t n_pairs,
+                                      float *dq_acc, float *dk_acc, float *dv_acc, const zp_shape *sh, void *ws,
+                                      size_t ws_bytes, void *stream) {
+  int rc = check_shape(sh);
+  if (rc) return rc;
+  if (n_pairs < 0) return ZP_EINVAL;
+  if (n_pairs == 0 || sh->T == 0) return ZP_OK;
+  if (!dout || !q || !k || !v || !o || !lse || !pairs || !dq_acc || !dk_acc || !dv_acc) return ZP_EINVAL;
+  if (!aligned16(dout) || !aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(dq_acc) ||
+      !aligned16(dk_acc) || !aligned16(dv_acc))
+    return ZP_EINVAL;
+  if (check_stride(q_stride, sh->Hq, sh->d) || check_stride(o_stride, sh->Hq, sh->d) ||
+      check_stride(do_stride, sh->Hq, sh->d) || check_stride(k_stride, sh->Hkv, sh->d) ||
+      check_stride(v_stride, sh->Hkv, sh->d))
+    return ZP_EINVAL;
+  // one ring round: every Q row and every KV row may appear in at most one pair (the kernels add without atomics)
+  std::vector<std::pair<int32_t, int32_t>> qr, kr;
+  for (int i = 0; i < n_pairs; i++) {
+    const zp_pair &pr = pairs[i];
+    if (pr.q_len < 0 || pr.k_len < 0 || pr.q_tok0 < 0 || pr.k_tok0 < 0 || pr.q_pos0 < 0 || pr.k_pos0 < 0) return ZP_EINVAL;
+    if ((int64_t)pr.q_tok0 + pr.q_len > sh->T || (int64_t)pr.k_tok0 + pr.k_len > sh->T) return ZP_EINVAL;
+    if (pr.q_len > 0) qr.push_back({pr.q_tok0, pr.q_tok0 + pr.q_len});
+    if (pr.k_len > 0) kr.push_back({pr.k_tok0, pr.k_tok0 + pr.k_len});
+  }
+  for (auto *ranges : {&qr, &kr}) {
+    std::sort(ranges->begin(), ranges->end());
+    for (size_t i = 1; i < ranges->size(); i++)
+      if ((*ranges)[i].first < (*ranges)[i - 1].second) return ZP_EINVAL;
+  }
+  const int bmq = zp_attn_bwd_block_rows(sh->d, 0), bnk = zp_attn_bwd_block_rows(sh->d, 1);
+  std::vector<CostTile> qt, kt;
+  plan_pairs_bwd(pairs, n_pairs, bmq, bnk, qt, kt);
+  const size_t tile_bytes = align256((qt.size() + kt.size()) * sizeof(zp_tile));
+  const size_t dvec_bytes = align256((size_t)sh->Hq * (size_t)sh->T * sizeof(float));
+  if ((rc = check_ws(ws, ws_bytes, tile_bytes + 2 * dvec_bytes))) return rc;
+  std::vector<CostTile> all(qt);
+  all.insert(all.end(), kt.begin(), kt.end());
+  if ((rc = upload_tiles(all, ws, (hipStream_t)stream))) return rc;
+  zp_bwd_params p{};
+  p.q = (const __bf16 *)q; p.k = (const __bf16 *)k; p.v = (const __bf16 *)v; p.o = (const __bf16 *)o;
+  p.dout = (const __bf16 *)dout;
+  p.q_stride = q_stride; p.k_stride = k_stride; p.v_stride = v_stride; p.o_stride = o_stride; p.do_stride = do_stride;
+  p.lse = lse;
+  p.dvec = (float *)((char *)ws + tile_bytes);
+  p.lse2 = (float *)((char *)ws + tile_bytes + dvec_bytes);
+  p.dq_tiles = (const zp_tile *)ws;
+  p.kv_tiles = (const zp_tile *)ws + qt.size();
+  p.n_dq_tiles = (int32_t)qt.size(); p.n_kv_tiles = (int32_t)kt.size();
+  p.Hq = sh->Hq; p.Hkv = sh->Hkv; p.grp = sh->Hq / sh->Hkv; p.T = sh->T;
+  p.scale = eff_scale(sh); p.scale_log2 = p.scale * 1.4426950408889634f;
+  p.dq = (__bf16 *)dq_acc; p.dk = (__bf16 *)dk_acc; p.dv = (__bf16 *)dv_acc;
+  p.dq_stride = (int64_t)sh->Hq * sh->d; p.dkv_stride = (int64_t)sh->Hkv * sh->d;
+  p.accumulate = 1;
+  hipError_t e = (hipError_t)zp_launch_attn_bwd(&p, sh->d, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, "chunk_attn_partial_bwd launch");
+  return ZP_OK;
+}
+
+extern "C" int zp_accum_to_bf16(const float *src, void *dst, int64_t n, void *stream) {
+  if (n < 0 || (n % 8)) return ZP_EINVAL;
+  if (n == 0) return ZP_OK;
+  if (!src || !dst || !aligned16(src) || !aligned16(dst)) return ZP_EINVAL;
+  hipError_t e = (hipError_t)zp_launch_accum_to_bf16(src, dst, n, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, "accum_to_bf16 launch");
   return ZP_OK;
 }

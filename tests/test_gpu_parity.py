@@ -186,3 +186,57 @@ def test_bwd_custom_scale_and_deterministic():
     a = B.varlen_attn_bwd(do, q, k, v, o, lse, cu); b = B.varlen_attn_bwd(do, q, k, v, o, lse, cu)
     for x, y in zip(a, b):
         assert torch.equal(x.view(torch.int16), y.view(torch.int16))
+
+
+# ---- chunked backward --------------------------------------------------------------------------------
+def run_chunked_bwd(lengths, which, C, Hq, Hkv, d, seed, scale=0.0):
+    """Ring rounds of the chunked sequence `which` (Sec. 3.2): each round is one call that adds its pairs'
+    contributions; after the last round the accumulators hold that sequence's rows of the whole backward."""
+    (q, k, v, do), cu = make(lengths, Hq, Hkv, d, seed, with_dout=True)
+    o, lse = B.varlen_attn_fwd(q, k, v, cu, scale=scale)
+    t0, L = int(cu[which]), lengths[which]
+    pairs, _, _ = B.chunk_pairs(t0, L, C)
+    acc = [torch.zeros(x.shape, dtype=torch.float32, device=DEV) for x in (q, k, v)]
+    for rnd in B.ring_rounds(pairs, C):
+        B.chunk_attn_partial_bwd(do, q, k, v, o, lse, rnd, *acc, scale=scale)
+    torch.cuda.synchronize()
+    rdq, rdk, rdv = oracle.varlen_attn_bwd(widen(do), widen(q), widen(k), widen(v), cu, scale=scale or None)
+    sl = slice(t0, t0 + L)
+    for name, a, r in zip(("dQ", "dK", "dV"), acc, (rdq, rdk, rdv)):
+        assert_close(name, a.double().cpu().numpy()[sl], r[sl])
+        assert not a[:t0].any() and not a[t0 + L:].any()      # rows of the other sequences are untouched
+        bits = B.accum_to_bf16(a).view(torch.int16).cpu().numpy().view(np.uint16)
+        assert np.array_equal(bits, oracle.f32_to_bf16_bits(a.cpu().numpy()))     # the final rounding is bit-exact
+    return acc
+
+
+@pytest.mark.parametrize("L,C,Hq,Hkv,d", [(1000, 4, 4, 2, 128), (777, 3, 2, 2, 64), (130, 8, 2, 1, 128), (5, 8, 2, 1, 64),
+                                          (600, 1, 4, 4, 128), (1500, 2, 8, 2, 128), (2100, 16, 2, 1, 128)])
+def test_chunked_backward_rounds_equal_whole_backward(L, C, Hq, Hkv, d):
+    run_chunked_bwd([50, L, 31], 1, C, Hq, Hkv, d, 37)
+
+
+def test_chunked_backward_custom_scale_and_single_round_against_oracle():
+    run_chunked_bwd([300], 0, 2, 4, 2, 128, 41, scale=0.07)
+    # one off-diagonal round on its own, against the oracle's pair-restricted sums
+    lengths = [900]
+    (q, k, v, do), cu = make(lengths, 4, 2, 128, 43, with_dout=True)
+    o, lse = B.varlen_attn_fwd(q, k, v, cu)
+    pairs, _, _ = B.chunk_pairs(0, 900, 4)
+    rnd = B.ring_rounds(pairs, 4)[2]
+    acc = [torch.zeros(x.shape, dtype=torch.float32, device=DEV) for x in (q, k, v)]
+    B.chunk_attn_partial_bwd(do, q, k, v, o, lse, rnd, *acc)
+    B.chunk_attn_partial_bwd(do, q, k, v, o, lse, rnd, *acc)     # a second call adds the same again
+    torch.cuda.synchronize()
+    ro, rl = oracle.varlen_attn_fwd(widen(q), widen(k), widen(v), cu)
+    D = np.einsum("thc,thc->ht", widen(do), widen(o))           # the device's own O, as the kernel reads it
+    opairs, _, _ = oracle.causal_pairs(0, 900, 4)
+    by = {}
+    n = 0
+    for qc in range(4):
+        for kc in range(qc + 1):
+            by[(qc, kc)] = opairs[n]; n += 1
+    ref = [np.zeros(x.shape) for x in (q, k, v)]
+    oracle.chunk_attn_partial_bwd(widen(do), widen(q), widen(k), widen(v), [by[pr] for pr in oracle.ring_rounds(4)[2]], rl, D, *ref)
+    for name, a, r in zip(("dQ", "dK", "dV"), acc, ref):
+        assert_close(name, a.double().cpu().numpy(), 2 * r)

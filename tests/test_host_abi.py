@@ -77,6 +77,32 @@ def test_remap_and_merge_validation_without_device():
                                 1 << 12, 1 << 20, None) == -1
 
 
+def test_chunked_backward_validation_without_device():
+    L = B.lib()
+    sh = B.make_shape(200, 0, 4, 4, 64)
+    A = 1 << 12
+
+    def rc(pairs, ws=A, wsb=1 << 22, dq=A):
+        arr = (B.ZpPair * len(pairs))()
+        for n, (qt, ql, kt, kl) in enumerate(pairs):
+            arr[n].q_tok0, arr[n].q_len, arr[n].k_tok0, arr[n].k_len, arr[n].q_pos0, arr[n].k_pos0 = qt, ql, kt, kl, qt, kt
+        return L.chunk_attn_partial_bwd(A, A, A, A, A, A, 256, 256, 256, 256, 256, arr, len(pairs), dq, A, A,
+                                        ctypes.byref(sh), ws, wsb, None)
+
+    assert rc([(100, 50, 0, 50), (120, 50, 50, 50)]) == -1      # two pairs share query rows: the adds would race
+    assert rc([(100, 50, 0, 50), (150, 50, 40, 50)]) == -1      # two pairs share key rows
+    assert rc([(100, 101, 0, 50)]) == -1                        # queries past T
+    assert rc([(100, 50, 0, 50)], dq=0) == -1                   # null accumulator
+    assert rc([(100, 50, 0, 50)], dq=A + 4) == -1               # misaligned accumulator
+    assert rc([(100, 50, 0, 50)], ws=0) == -3
+    assert rc([(100, 50, 0, 50)], wsb=64) == -3
+    assert rc([]) == 0                                          # empty round
+    assert L.zp_accum_to_bf16(A, A, 12, None) == -1             # not a multiple of 8 elements
+    assert L.zp_accum_to_bf16(0, A, 64, None) == -1
+    assert L.zp_accum_to_bf16(A, A, 0, None) == 0
+    assert B.workspace_bytes(B.FN_PARTIAL_BWD, sh, None, 3) > 2 * 4 * 200 * 4
+
+
 @pytest.mark.parametrize("L,C", [(101, 4), (38400, 4), (7, 3), (64, 1), (5, 8)])
 def test_chunk_pairs_match_oracle_enumeration(L, C):
     pairs, merges, rows = B.chunk_pairs(17, L, C)

@@ -299,3 +299,56 @@ def test_balanced_layout_is_a_permutation_moving_whole_sequences():
     cu = synth.cu_seqlens(lengths); pos = 0
     for s in order:
         assert np.array_equal(idx[pos:pos + lengths[s]], np.arange(cu[s], cu[s + 1])); pos += lengths[s]
+
+
+@pytest.mark.parametrize("C", [1, 2, 4])
+def test_chunked_backward_sums_to_whole_backward(C):
+    """Sec. 3.2 / 5.4: the per-pair backward contributions, with the merged row statistics, add up to the backward
+    of the whole sequence; within a round no Q chunk and no KV chunk appears twice."""
+    lengths = [29, 70]
+    q, k, v, do, cu = rand_case(lengths, 4, 2, 8, 101)
+    o, lse = oracle.varlen_attn_fwd(q, k, v, cu)
+    D = np.einsum("thc,thc->ht", do, o)
+    dq, dk, dv = oracle.varlen_attn_bwd(do, q, k, v, cu)
+    aq, ak, av = np.zeros_like(q), np.zeros_like(k), np.zeros_like(v)
+    for s, L in enumerate(lengths):
+        pairs, _, _ = oracle.causal_pairs(int(cu[s]), L, C)
+        order = [(qc, kc) for qc in range(C) for kc in range(qc + 1)]     # the enumeration order of causal_pairs
+        by = dict(zip(order, pairs))
+        for rnd in oracle.ring_rounds(C):
+            assert len({qc for qc, _ in rnd}) == len(rnd) and len({kc for _, kc in rnd}) == len(rnd)
+            oracle.chunk_attn_partial_bwd(do, q, k, v, [by[pr] for pr in rnd], lse, D, aq, ak, av)
+    assert sorted(pr for rnd in oracle.ring_rounds(C) for pr in rnd) == sorted((qc, kc) for qc in range(C) for kc in range(qc + 1))
+    assert np.abs(aq - dq).max() < 1e-12 and np.abs(ak - dk).max() < 1e-12 and np.abs(av - dv).max() < 1e-12
+
+
+def test_chunked_backward_single_pair_closed_form():
+    """One query row against one key chunk, d = 1, checked against the formulas written out by hand."""
+    q = np.array([[[0.5]], [[2.0]]]); k = np.array([[[1.0]], [[-1.0]]]); v = np.array([[[3.0]], [[5.0]]])
+    do = np.array([[[1.0]], [[2.0]]]); cu = np.array([0, 2], np.int32)
+    o, lse = oracle.varlen_attn_fwd(q, k, v, cu, scale=1.0)
+    D = np.einsum("thc,thc->ht", do, o)
+    aq, ak, av = np.zeros_like(q), np.zeros_like(k), np.zeros_like(v)
+    pair = dict(q_tok0=1, q_len=1, k_tok0=0, k_len=1, q_pos0=1, k_pos0=0, out_row0=0)   # row 1 against key 0 only
+    oracle.chunk_attn_partial_bwd(do, q, k, v, [pair], lse, D, aq, ak, av, scale=1.0)
+    p10 = np.exp(2.0 * 1.0) / (np.exp(2.0) + np.exp(-2.0))
+    ds = p10 * (2.0 * 3.0 - D[0, 1])
+    assert abs(aq[1, 0, 0] - ds * 1.0) < 1e-14 and abs(ak[0, 0, 0] - ds * 2.0) < 1e-14 and abs(av[0, 0, 0] - p10 * 2.0) < 1e-14
+    assert aq[0, 0, 0] == 0 and ak[1, 0, 0] == 0 and av[1, 0, 0] == 0
+
+
+def test_f32_to_bf16_rounding_pins():
+    """Round to nearest even on the 16 dropped bits: hand-picked bit patterns."""
+    f = lambda bits: np.array([bits], np.uint32).view(np.float32)
+    r = lambda bits: int(oracle.f32_to_bf16_bits(f(bits))[0])
+    assert r(0x3F800000) == 0x3F80            # 1.0
+    assert r(0x3F808000) == 0x3F80            # tie, keep even
+    assert r(0x3F818000) == 0x3F82            # tie, round up to even
+    assert r(0x3F808001) == 0x3F81            # above the tie
+    assert r(0x3F807FFF) == 0x3F80            # below the tie
+    assert r(0xBF818000) == 0xBF82            # sign is carried
+    assert r(0x7F7FFFFF) == 0x7F80            # largest float rounds to infinity
+    assert r(0x00000000) == 0 and r(0x80000000) == 0x8000
+    x = np.random.default_rng(3).standard_normal(4096).astype(np.float32)
+    back = oracle.bf16_bits_to_f64(oracle.f32_to_bf16_bits(x))
+    assert (np.abs(back - x) <= np.abs(x) * 2.0 ** -8).all()    # half an ulp of an 8-bit significand (7 stored bits)
