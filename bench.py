@@ -193,6 +193,23 @@ def cpu_baseline(job: Job, target_s: float = 15.0):
                       f"{len(heads)} query heads of KV group 0, {dt:.1f} s"}
 
 
+def mfma_sustained(iters: int = 60000):
+    """MFMA rate the chip holds on a register-only loop, with all-zero and with random operand values (context for
+    the roofline fraction: the clock drops under the switching power of real data)."""
+    out = {}
+    buf = torch.empty(256 * 256, dtype=torch.float32, device="cuda:0")
+    stream = torch.cuda.current_stream()
+    for name, rnd in (("zero_operands", False), ("random_operands", True)):
+        B.mfma_probe(2000, rnd, out=buf)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        B.mfma_probe(iters, rnd, out=buf)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        out[name] = B.MFMA_PROBE_FLOP_PER_ITER * iters / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -230,6 +247,7 @@ def main():
     ms_step = ev0.elapsed_time(ev1) / a.steps
     recs = B.profile_records()
     B.profile_enable(False)
+    sustained = mfma_sustained()
 
     by = {}
     for label, ms in recs:
@@ -240,7 +258,9 @@ def main():
     dom = max(attn, key=lambda k: attn[k]["ms_per_step"])
     ach = kernel_flops(job, dom) / (kern[dom]["avg_ms"] * 1e-3) / 1e12
     roofline = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": MEASURED_TRAFFIC_BYTES.get((a.workload, dom))}
+                "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": MEASURED_TRAFFIC_BYTES.get((a.workload, dom)),
+                "mfma_sustained_tflops": sustained,
+                "frac_of_sustained_random_operands": ach / sustained["random_operands"]}
     total_flops = job.flops_fwd + job.flops_bwd
     value = total_flops / (ms_step * 1e-3) / 1e12
     out = {

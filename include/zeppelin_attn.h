@@ -164,6 +164,15 @@ typedef struct {
 int zp_partition(const int32_t *lengths, int32_t S, int32_t P, int32_t N, int32_t L, zp_placement *out,
                  int32_t max_out, int32_t *n_out, int32_t *s1_final, int32_t *s0_final);
 
+/* Measurement aid: enqueues a register-only loop of bf16 MFMAs (256 workgroups x 4 waves, iters * 32 instructions of
+ * 32x32x16 per wave = 256 * 4 * iters * 32 * 32768 flop in total) with all-zero (random_operands = 0) or random
+ * operand values, so a caller that times the launch learns the MFMA rate the chip sustains on such data: the clock
+ * held under random operands is lower than under zeros. out: device, ZP_MFMA_PROBE_OUT_BYTES bytes, overwritten.
+ * iters in [1, 2^22]. Returns ZP_EINVAL on a null or misaligned pointer or iters out of range. */
+#define ZP_MFMA_PROBE_OUT_BYTES 262144
+#define ZP_MFMA_PROBE_FLOP_PER_ITER 1073741824.0 /* 256 * 4 * 32 * 32768 */
+int zp_mfma_probe(float *out, int32_t iters, int32_t random_operands, void *stream);
+
 /* Measurement aid: per-kernel durations from hipEvents recorded on the launch stream.
  * zp_profile_enable(1) clears the records and starts recording every kernel the library launches (one
  * record per launch, in launch order); zp_profile_enable(0) stops and clears. zp_profile_get() waits for

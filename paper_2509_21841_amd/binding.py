@@ -72,6 +72,8 @@ def lib() -> ctypes.CDLL:
                                          vp, vp, vp, ctypes.POINTER(ZpShape), vp, sz, vp]
     L.zp_accum_to_bf16.restype = ctypes.c_int
     L.zp_accum_to_bf16.argtypes = [vp, vp, i64, vp]
+    L.zp_mfma_probe.restype = ctypes.c_int
+    L.zp_mfma_probe.argtypes = [vp, i32, i32, vp]
     L.lse_merge.restype = ctypes.c_int
     L.lse_merge.argtypes = [vp, vp, i64, ctypes.POINTER(ZpMerge), i32, vp, i64, vp, ctypes.POINTER(ZpShape), vp, sz, vp]
     L.remap_tokens.restype = ctypes.c_int
@@ -250,6 +252,17 @@ def accum_to_bf16(src, dst=None, stream=None):
         dst = torch.empty(src.shape, dtype=torch.bfloat16, device=src.device)
     _check(lib().zp_accum_to_bf16(src.data_ptr(), dst.data_ptr(), src.numel(), _stream_ptr(stream)))
     return dst
+
+
+MFMA_PROBE_FLOP_PER_ITER = 256.0 * 4 * 32 * 32768.0
+
+
+def mfma_probe(iters: int, random_operands: bool, out=None, stream=None):
+    """Enqueues the register-only MFMA loop; the caller times it (MFMA_PROBE_FLOP_PER_ITER * iters flop)."""
+    if out is None:
+        out = torch.empty(256 * 256, dtype=torch.float32, device="cuda")
+    _check(lib().zp_mfma_probe(out.data_ptr(), int(iters), int(bool(random_operands)), _stream_ptr(stream)))
+    return out
 
 
 def ring_rounds(pairs, C: int):

@@ -301,42 +301,80 @@ __device__ __forceinline__ void dkdv_tile(const char *Qb, const char *Ob, const 
       for (int db = 0; db < DB; db++) tq[m][db] = lo.tr(Qb, qb, m, db);
   };
 
+  // A: S,dP(0); the row operands and seeds of block 1 are requested meanwhile
   load_seed(0);
   load_rows(0);
+  f32x16 s[2], dp[2];
+  bf16x8 pb[2][2], dsb[2][2];
+  bf16x8 aq1[KK], ao1[KK];
+  s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[0], kreg[0], s_seed[0], 0, 0, 0);
+  dp[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ao[0], vreg[0], dp_seed[0], 0, 0, 0);
 #pragma unroll
-  for (int qb = 0; qb < 2; qb++) {
-    f32x16 s, dp;
-    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[0], kreg[0], s_seed[qb], 0, 0, 0);
-    dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ao[0], vreg[0], dp_seed[qb], 0, 0, 0);
-#pragma unroll
-    for (int kk = 1; kk < KK; kk++) {
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[kk], kreg[kk], s, 0, 0, 0);
-      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ao[kk], vreg[kk], dp, 0, 0, 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    load_to(qb);                  // lands while P and dS are computed
-    if (qb == 0) load_seed(1);
-    __builtin_amdgcn_sched_barrier(0);
-    bf16x8 pb[2], dsb[2];
-    dkdv_pds<D, MASK>(s, dp, qb, hi, qpos0, kpos, qpos_end, c_log2, pb, dsb);
-    __builtin_amdgcn_sched_barrier(0);
-    load_tq(qb);                  // lands while dV accumulates
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int m = 0; m < 2; m++)
-#pragma unroll
-      for (int db = 0; db < DB; db++)
-        dv_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(to[m][db], pb[m], dv_acc[db], 0, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
-    if (qb == 0) load_rows(1);    // lands while dK accumulates
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int m = 0; m < 2; m++)
-#pragma unroll
-      for (int db = 0; db < DB; db++)
-        dk_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq[m][db], dsb[m], dk_acc[db], 0, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
+  for (int kk = 1; kk < KK; kk++) {
+    s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[kk], kreg[kk], s[0], 0, 0, 0);
+    dp[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ao[kk], vreg[kk], dp[0], 0, 0, 0);
   }
+  load_seed(1);
+#pragma unroll
+  for (int kk = 0; kk < KK; kk++) aq1[kk] = lo.rows(Qb, 1, kk);
+#pragma unroll
+  for (int kk = 0; kk < KK; kk++) ao1[kk] = lo.rows(Ob, 1, kk);
+#pragma unroll
+  for (int i = 0; i < 2 * KK; i++) { ZP_SGB(ZP_SG_MFMA, 1); ZP_SGB(ZP_SG_DSREAD, 2); }
+  __builtin_amdgcn_sched_barrier(0);
+
+  // B: S,dP(1) interleaved with P,dS(0); the transposed operands of block 0 are requested meanwhile
+  s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq1[0], kreg[0], s_seed[1], 0, 0, 0);
+  dp[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ao1[0], vreg[0], dp_seed[1], 0, 0, 0);
+#pragma unroll
+  for (int kk = 1; kk < KK; kk++) {
+    s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq1[kk], kreg[kk], s[1], 0, 0, 0);
+    dp[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ao1[kk], vreg[kk], dp[1], 0, 0, 0);
+  }
+  dkdv_pds<D, MASK>(s[0], dp[0], 0, hi, qpos0, kpos, qpos_end, c_log2, pb[0], dsb[0]);
+  load_to(0);
+  load_tq(0);
+#pragma unroll
+  for (int i = 0; i < 2 * KK; i++) { ZP_SGB(ZP_SG_MFMA, 1); ZP_SGB(ZP_SG_TRANS, 1); ZP_SGB(ZP_SG_VALU, 3); ZP_SGB(ZP_SG_DSREAD, 2); }
+  __builtin_amdgcn_sched_barrier(0);
+
+  // C: dV,dK(0) interleaved with P,dS(1); the transposed operands of block 1 are requested meanwhile
+  bf16x8 to1[2][DB], tq1[2][DB];
+#pragma unroll
+  for (int m = 0; m < 2; m++)
+#pragma unroll
+    for (int db = 0; db < DB; db++)
+      dv_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(to[m][db], pb[0][m], dv_acc[db], 0, 0, 0);
+#pragma unroll
+  for (int m = 0; m < 2; m++)
+#pragma unroll
+    for (int db = 0; db < DB; db++)
+      dk_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq[m][db], dsb[0][m], dk_acc[db], 0, 0, 0);
+  dkdv_pds<D, MASK>(s[1], dp[1], 1, hi, qpos0, kpos, qpos_end, c_log2, pb[1], dsb[1]);
+#pragma unroll
+  for (int m = 0; m < 2; m++)
+#pragma unroll
+    for (int db = 0; db < DB; db++) to1[m][db] = lo.tr(Ob, 1, m, db);
+#pragma unroll
+  for (int m = 0; m < 2; m++)
+#pragma unroll
+    for (int db = 0; db < DB; db++) tq1[m][db] = lo.tr(Qb, 1, m, db);
+#pragma unroll
+  for (int i = 0; i < 4 * DB; i++) { ZP_SGB(ZP_SG_MFMA, 1); ZP_SGB(ZP_SG_TRANS, 1); ZP_SGB(ZP_SG_VALU, 3); ZP_SGB(ZP_SG_DSREAD, 2); }
+  __builtin_amdgcn_sched_barrier(0);
+
+  // D: dV,dK(1)
+#pragma unroll
+  for (int m = 0; m < 2; m++)
+#pragma unroll
+    for (int db = 0; db < DB; db++)
+      dv_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(to1[m][db], pb[1][m], dv_acc[db], 0, 0, 0);
+#pragma unroll
+  for (int m = 0; m < 2; m++)
+#pragma unroll
+    for (int db = 0; db < DB; db++)
+      dk_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq1[m][db], dsb[1][m], dk_acc[db], 0, 0, 0);
+  __builtin_amdgcn_sched_barrier(0);
 }
 
 template <int D>

@@ -240,3 +240,10 @@ def test_chunked_backward_custom_scale_and_single_round_against_oracle():
     oracle.chunk_attn_partial_bwd(widen(do), widen(q), widen(k), widen(v), [by[pr] for pr in oracle.ring_rounds(4)[2]], rl, D, *ref)
     for name, a, r in zip(("dQ", "dK", "dV"), acc, ref):
         assert_close(name, a.double().cpu().numpy(), 2 * r)
+
+
+def test_mfma_probe_runs_and_is_deterministic():
+    a = B.mfma_probe(50, True).clone(); b = B.mfma_probe(50, True)
+    torch.cuda.synchronize()
+    assert torch.isfinite(a).all() and torch.equal(a, b) and a.abs().max() > 0
+    assert not B.mfma_probe(50, False).any()
