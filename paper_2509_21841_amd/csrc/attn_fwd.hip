@@ -7,6 +7,7 @@
 // and the rescale factor is a per-lane scalar. The bf16 probabilities are already laid out as the B
 // operand of O^T += V^T P^T (k-slot i of MFMA m <-> accumulator register 8m+i), and V^T comes from the
 // row-major V tile in LDS through the transposing LDS read with the matching key order.
+#include <type_traits>
 #include "zp_common.h"
 
 namespace {
@@ -44,10 +45,14 @@ __device__ __forceinline__ void fwd_tile(const char *Kb, const char *Vb, const b
       if (j + 32 >= nvis_lane) s1[r] = -INFINITY;
     }
   }
-  float tmax = fmaxf(s0[0], s1[0]);
+  // two chains of three-operand maxima over the lane's 32 scores
+  float ta = zp_max3(s0[0], s0[1], s1[0]);
+  float tb = zp_max3(s1[1], s1[2], s1[3]);
 #pragma unroll
-  for (int r = 1; r < 16; r++) tmax = fmaxf(tmax, fmaxf(s0[r], s1[r]));
-  tmax = zp_pair_max(tmax);
+  for (int r = 2; r < 16; r += 2) ta = zp_max3(ta, s0[r], s0[r + 1]);
+#pragma unroll
+  for (int r = 4; r < 16; r += 2) tb = zp_max3(tb, s1[r], s1[r + 1]);
+  const float tmax = zp_pair_max(zp_max3(ta, tb, tb));
   const float tmc = tmax * c_log2;
   // the reference maximum moves only when the tile maximum exceeds it by more than 2^8
   if (__builtin_amdgcn_ballot_w64(tmc > mc + 8.0f) != 0) {
@@ -61,15 +66,19 @@ __device__ __forceinline__ void fwd_tile(const char *Kb, const char *Vb, const b
       for (int r = 0; r < 16; r++) o_acc[i][r] *= alpha;
   }
   const float neg_mc = (mc == -INFINITY) ? 0.f : -mc;
+  // the row sum is taken over the unrounded probabilities: LSE has to hold to 1e-3 also for rows with few keys
   bf16x8 pb[2][2];
+  float l1 = 0.f;
 #pragma unroll
   for (int r = 0; r < 16; r++) {
     const float p0 = zp_exp2(__builtin_fmaf(s0[r], c_log2, neg_mc));
     const float p1 = zp_exp2(__builtin_fmaf(s1[r], c_log2, neg_mc));
-    l_sum += p0 + p1;
+    l_sum += p0;
+    l1 += p1;
     pb[0][r >> 3][r & 7] = (__bf16)p0;
     pb[1][r >> 3][r & 7] = (__bf16)p1;
   }
+  l_sum += l1;
 #pragma unroll
   for (int kb = 0; kb < 2; kb++)
 #pragma unroll
@@ -143,8 +152,10 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   zp_wait_async();
   __syncthreads();
 
-  for (int it = 0; it < n_kt; it++) {
-    const int j0 = it * BN, buf = it & 1;
+  // one key tile out of LDS buffer BUF (a compile-time constant, so every LDS address is register + immediate)
+  auto key_tile = [&](int it, auto BUF) {
+    constexpr int buf = decltype(BUF)::value;
+    const int j0 = it * BN;
     if (it + 1 < n_kt) {
       kst.issue(Ks + (buf ^ 1) * C::TILEB, j0 + BN, t.k_len);
       vst.issue(Vs + (buf ^ 1) * C::TILEB, j0 + BN, t.k_len);
@@ -157,7 +168,13 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     }
     zp_wait_async();
     __syncthreads();
+  };
+  int it = 0;
+  for (; it + 1 < n_kt; it += 2) {
+    key_tile(it, std::integral_constant<int, 0>{});
+    key_tile(it + 1, std::integral_constant<int, 1>{});
   }
+  if (it < n_kt) key_tile(it, std::integral_constant<int, 0>{});
 
   // epilogue: normalise, write O and LSE
   const float l_tot = zp_pair_sum(l_sum);

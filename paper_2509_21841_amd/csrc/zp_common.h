@@ -53,6 +53,12 @@ __device__ __forceinline__ void zp_block_to_unit(int bid, int grp, int &unit, in
 
 __device__ __forceinline__ float zp_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Three-operand maximum in one VALU operation (operands are finite or -inf here, never NaN).
+__device__ __forceinline__ float zp_max3(float a, float b, float c) {
+  float d;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+  return d;
+}
 // max / sum across the two lanes l and l^32 that hold the two halves of one 32x32 MFMA column.
 __device__ __forceinline__ float zp_pair_max(float x) {
   auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
