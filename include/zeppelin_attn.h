@@ -164,6 +164,24 @@ typedef struct {
 int zp_partition(const int32_t *lengths, int32_t S, int32_t P, int32_t N, int32_t L, zp_placement *out,
                  int32_t max_out, int32_t *n_out, int32_t *s1_final, int32_t *s0_final);
 
+/* Host helper: transfer plan of the remapping layer (Sec. 3.4, Eq. 2). A[d]: tokens per rank in the attention layout;
+ * rank r sits in node r / P. The balanced target is B_i = floor(T/d) + (i < T mod d). Writes M[d*d] (row-major,
+ * M[i*d+j] = tokens rank i sends to rank j) with row sums max(A-B,0), column sums max(B-A,0), minimising
+ * max_i sum_j T_ij * M_ij where T_ij = b_inter across nodes and b_intra inside a node (integer costs per token,
+ * 1 <= b_intra <= b_inter), and the minimum to *objective (optional). Among the optimal plans it picks the one that
+ * exports from every node only its excess and matches senders to receivers in ascending rank order.
+ * Returns ZP_EINVAL on null pointers, d < 1, P < 1, a negative count or costs out of order. */
+int zp_remap_plan(const int32_t *A, int32_t d, int32_t P, int32_t b_intra, int32_t b_inter, int32_t *M,
+                  int64_t *objective);
+
+/* Host helper: the token permutation of a transfer plan, for remap_tokens. Positions count over the concatenation of
+ * the rank buffers. A sender parts with the tail of its attention-layout buffer, cut into one run per destination in
+ * ascending rank order; a rank's balanced buffer is its kept head followed by the arrivals in ascending source order.
+ * Writes idx[n_idx] (n_idx = sum A): idx[balanced position] = attention-layout position, i.e. remap_tokens mode 0
+ * takes the attention layout to the balanced one and mode 1 takes it back. Returns ZP_EINVAL if M does not move
+ * exactly every surplus and deficit or n_idx != sum A. */
+int zp_remap_indices(const int32_t *A, const int32_t *M, int32_t d, int32_t *idx, int64_t n_idx);
+
 /* Measurement aid: enqueues a register-only loop of bf16 MFMAs (256 workgroups x 4 waves, iters * 32 instructions of
  * 32x32x16 per wave = 256 * 4 * iters * 32 * 32768 flop in total) with all-zero (random_operands = 0) or random
  * operand values, so a caller that times the launch learns the MFMA rate the chip sustains on such data: the clock

@@ -72,6 +72,10 @@ def lib() -> ctypes.CDLL:
                                          vp, vp, vp, ctypes.POINTER(ZpShape), vp, sz, vp]
     L.zp_accum_to_bf16.restype = ctypes.c_int
     L.zp_accum_to_bf16.argtypes = [vp, vp, i64, vp]
+    L.zp_remap_plan.restype = ctypes.c_int
+    L.zp_remap_plan.argtypes = [vp, i32, i32, i32, i32, vp, ctypes.POINTER(i64)]
+    L.zp_remap_indices.restype = ctypes.c_int
+    L.zp_remap_indices.argtypes = [vp, vp, i32, vp, i64]
     L.zp_mfma_probe.restype = ctypes.c_int
     L.zp_mfma_probe.argtypes = [vp, i32, i32, vp]
     L.lse_merge.restype = ctypes.c_int
@@ -330,6 +334,27 @@ def profile_records():
         _check(lib().zp_profile_get(i, buf, 64, ctypes.byref(ms)))
         out.append((buf.value.decode(), float(ms.value)))
     return out
+
+
+def remap_plan(A, P: int, b_intra: int = 1, b_inter: int = 1):
+    """Host helper: transfer matrix of the remapping layer -> (M as a d x d int32 array, objective)."""
+    A = np.ascontiguousarray(A, dtype=np.int32)
+    d = len(A)
+    M = np.zeros((d, d), np.int32)
+    obj = ctypes.c_int64(0)
+    _check(lib().zp_remap_plan(A.ctypes.data_as(ctypes.c_void_p), d, int(P), int(b_intra), int(b_inter),
+                               M.ctypes.data_as(ctypes.c_void_p), ctypes.byref(obj)))
+    return M, int(obj.value)
+
+
+def remap_indices(A, M):
+    """Host helper: idx[balanced position] = attention-layout position for a transfer matrix M."""
+    A = np.ascontiguousarray(A, dtype=np.int32)
+    M = np.ascontiguousarray(M, dtype=np.int32)
+    idx = np.zeros(int(A.sum()), np.int32)
+    _check(lib().zp_remap_indices(A.ctypes.data_as(ctypes.c_void_p), M.ctypes.data_as(ctypes.c_void_p), len(A),
+                                  idx.ctypes.data_as(ctypes.c_void_p), len(idx)))
+    return idx
 
 
 def partition(lengths, P: int, N: int, L: int):

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libzeppelin_attn.so")
-SOURCES = ["zp_api.hip", "attn_fwd.hip", "attn_bwd.hip", "lse_merge.hip", "remap.hip", "mfma_probe.hip", "zp_partition.cpp"]
+SOURCES = ["zp_api.hip", "attn_fwd.hip", "attn_bwd.hip", "lse_merge.hip", "remap.hip", "mfma_probe.hip", "zp_partition.cpp", "zp_remap_plan.cpp"]
 # packed-fp32 VALU forms are switched off on purpose for this target
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument",

@@ -45,6 +45,30 @@ def test_remap_empty_and_layout_round_trip():
     assert torch.equal(B.remap_tokens(qa, idx_d, 1).view(torch.int16), q.view(torch.int16))
 
 
+def test_remap_with_planned_indices_balances_the_ranks():
+    """Transfer plan (Sec. 3.4) -> permutation -> device remap: rank slabs of the balanced layout hold exactly the
+    tokens the oracle's selection rule names, and the inverse remap restores the attention layout."""
+    from oracle import remap_planner as RP
+    rng = np.random.default_rng(3)
+    P, N = 4, 2
+    A = rng.integers(0, 700, size=P * N).tolist()
+    M, _ = B.remap_plan(A, P, 1, 6)
+    idx = B.remap_indices(A, M)
+    assert np.array_equal(idx, RP.remap_indices(A, M))
+    T = int(sum(A))
+    x = synth.normal_bf16((T, 2, 64), 21, 1, DEV)
+    idx_d = torch.from_numpy(idx).to(DEV)
+    bal = B.remap_tokens(x, idx_d, 0)
+    assert np.array_equal(synth.bf16_bits(bal), oracle.remap_tokens(synth.bf16_bits(x), idx, 0))
+    assert torch.equal(B.remap_tokens(bal, idx_d, 1).view(torch.int16), x.view(torch.int16))
+    # rank r's balanced slab: its own head, then arrivals; sizes are the balanced targets
+    offB = np.concatenate([[0], np.cumsum(RP.targets(A))]); offA = np.concatenate([[0], np.cumsum(A)])
+    for r in range(P * N):
+        own = idx[offB[r]:offB[r + 1]]
+        kept = min(A[r], RP.targets(A)[r])
+        assert np.array_equal(own[:kept], np.arange(offA[r], offA[r] + kept))
+
+
 # ---- merge -------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("Hq,d,n,parts", [(4, 64, 37, 3), (32, 128, 300, 4), (2, 128, 9, 1), (3, 64, 20, 8), (2, 128, 11, 16)])
 def test_lse_merge_matches_oracle(Hq, d, n, parts):
