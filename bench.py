@@ -37,6 +37,11 @@ WORKLOADS = {
     "longtail-128k-gqa32x8": dict(T=131072, Hq=32, Hkv=8, d=128, seed=1003, mix="longtail", C=4, bwd=True, remap=True),
     "lognormal-64k-mha32": dict(T=65536, Hq=32, Hkv=32, d=128, seed=1002, mix="lognormal", C=0, bwd=True, remap=False),
     "lognormal-256k-gqa64x8": dict(T=262144, Hq=64, Hkv=8, d=128, seed=1005, mix="lognormal", C=0, bwd=True, remap=True),
+    # batches drawn from the length histograms of the paper's three corpora (Table 2), 7B-like multi-head attention;
+    # sequences of 16K tokens and more run as 4 chunks + merge
+    "arxiv-128k-mha32": dict(T=131072, Hq=32, Hkv=32, d=128, seed=1011, mix="table2:arxiv", C=4, bwd=True, remap=True),
+    "github-128k-mha32": dict(T=131072, Hq=32, Hkv=32, d=128, seed=1012, mix="table2:github", C=4, bwd=True, remap=True),
+    "prolong64k-128k-mha32": dict(T=131072, Hq=32, Hkv=32, d=128, seed=1013, mix="table2:prolong64k", C=4, bwd=True, remap=True),
     # forward of what ONE device of an 8-device node computes after the hierarchical partitioner has placed the
     # 128K long-tail batch (capacity 20480 tokens per device): its local sequences whole, and for every ring
     # sequence the Q chunks of its ring rank against their causal KV chunks, merged by LSE
@@ -56,7 +61,9 @@ class Job:
         w = WORKLOADS[name]
         self.name, self.w, self.dev = name, w, dev
         T, Hq, Hkv, d = w["T"], w["Hq"], w["Hkv"], w["d"]
-        if w["mix"] == "longtail":
+        if w["mix"].startswith("table2:"):
+            lin_lengths = synth.lengths_table2(T, w["seed"], w["mix"].split(":")[1])
+        elif w["mix"] == "longtail":
             lin_lengths, _ = synth.lengths_longtail(T, w["seed"])
         else:
             lin_lengths = synth.lengths_lognormal(T, w["seed"])

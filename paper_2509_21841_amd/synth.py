@@ -79,6 +79,33 @@ def lengths_longtail(total: int, seed: int, p_long: float = 0.1, short=(128, 409
             return out, is_long
 
 
+# Proportion of sequences per length bin (Table 2); bin k covers [edge[k], edge[k+1]) tokens. The GitHub row adds up
+# to 0.945 as printed and is renormalised; inside a bin lengths are drawn uniformly (the paper does not say).
+TABLE2_EDGES = [64, 1024, 2048, 4096, 8192, 16384, 32768, 65536, 131072, 262144]
+TABLE2 = {
+    "arxiv": [0.032, 0.03, 0.08, 0.219, 0.338, 0.224, 0.077, 0.0, 0.0],
+    "github": [0.0, 0.34, 0.095, 0.104, 0.107, 0.102, 0.088, 0.064, 0.045],
+    "prolong64k": [0.231, 0.042, 0.021, 0.012, 0.013, 0.008, 0.673, 0.0, 0.0],
+}
+
+
+def lengths_table2(total: int, seed: int, dataset: str, multiple: int = 64):
+    """Lengths drawn bin by bin from a Table 2 histogram until `total` tokens are packed. Lengths are rounded down to a
+    multiple of `multiple` (>= multiple); a draw that does not fit takes what is left of the budget."""
+    p = np.asarray(TABLE2[dataset], dtype=np.float64)
+    p = p / p.sum()
+    r = _rng(seed, 0)
+    out, left = [], int(total)
+    while left > 0:
+        k = int(r.choice(len(p), p=p))
+        L = int(r.integers(TABLE2_EDGES[k], TABLE2_EDGES[k + 1]))
+        L = max(multiple, (L // multiple) * multiple)
+        L = min(L, left)
+        out.append(L)
+        left -= L
+    return out
+
+
 def cu_seqlens(lengths) -> np.ndarray:
     cu = np.zeros(len(lengths) + 1, np.int32)
     cu[1:] = np.cumsum(np.asarray(lengths, np.int64))

@@ -125,3 +125,15 @@ def test_rank_share_matches_ring_schedule(G):
         want = sorted(pr for rnd in sched[rank] for pr in rnd)
         assert got == want
         assert sorted(m.out_tok0 for m in merges) == sorted({b[rank], b[C - 1 - rank]})
+
+
+def test_table2_length_mixes():
+    """The synthetic batches follow the printed histograms (GitHub renormalised) and pack the budget exactly."""
+    from paper_2509_21841_amd import synth
+    for name, probs in synth.TABLE2.items():
+        L = synth.lengths_table2(131072, 5, name)
+        assert sum(L) == 131072 and min(L) >= 1
+        big = synth.lengths_table2(1 << 30, 7, name)[:-1]          # the last draw is cut by the budget
+        hist = np.histogram(big, bins=synth.TABLE2_EDGES)[0] / len(big)
+        want = np.asarray(probs) / sum(probs)
+        assert np.abs(hist - want).max() < 0.02, (name, hist, want)
