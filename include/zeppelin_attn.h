@@ -104,6 +104,18 @@ int chunk_attn_partial(const void *q, const void *k, const void *v, int64_t q_st
                        int64_t v_stride, const zp_pair *pairs_host, int32_t n_pairs, float *o_part, float *lse_part,
                        int64_t part_rows, const zp_shape *sh, void *ws, size_t ws_bytes, void *stream);
 
+/* Chunk-pair attention merged in place (Sec. 3.2: a ring rank folds every round's result into what it holds).
+ * Like chunk_attn_partial, but instead of writing one partial per pair it combines each pair's result with the
+ * running rows of its queries: o_run [T][Hq][d] fp32 (contiguous) holds outputs normalised by their own softmax sum,
+ * lse_run [Hq][T] fp32 their natural-log LSE; after the call they hold the attention over the keys seen so far plus
+ * this pair's keys (LSE = log(exp(LSE_run) + exp(LSE_pair)), O weighted by exp(LSE_x - LSE)). Start from
+ * lse_run = -inf (o_run may then hold anything). out_row0 of the pairs is ignored. A query row may appear in ONE pair
+ * of a call only (ZP_EINVAL otherwise): the rows are read, merged and written back without atomics. Workspace:
+ * zp_workspace_bytes(ZP_FN_PARTIAL, ...). */
+int chunk_attn_update(const void *q, const void *k, const void *v, int64_t q_stride, int64_t k_stride, int64_t v_stride,
+                      const zp_pair *pairs_host, int32_t n_pairs, float *o_run, float *lse_run, const zp_shape *sh,
+                      void *ws, size_t ws_bytes, void *stream);
+
 /* Backward of one ring round of chunk pairs (Sec. 3.2 rounds, Sec. 5.4: the backward runs them in reverse): for
  * every pair and head, with P_ij = exp(scale q_i.k_j - LSE_i) over the pair's causally visible (i, j), LSE the
  * MERGED log-sum-exp of the whole row and D_i = dO_i.O_i from the merged O,

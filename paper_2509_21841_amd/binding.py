@@ -67,6 +67,9 @@ def lib() -> ctypes.CDLL:
     L.chunk_attn_partial.restype = ctypes.c_int
     L.chunk_attn_partial.argtypes = [vp, vp, vp, i64, i64, i64, ctypes.POINTER(ZpPair), i32, vp, vp, i64,
                                      ctypes.POINTER(ZpShape), vp, sz, vp]
+    L.chunk_attn_update.restype = ctypes.c_int
+    L.chunk_attn_update.argtypes = [vp, vp, vp, i64, i64, i64, ctypes.POINTER(ZpPair), i32, vp, vp,
+                                    ctypes.POINTER(ZpShape), vp, sz, vp]
     L.chunk_attn_partial_bwd.restype = ctypes.c_int
     L.chunk_attn_partial_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, ctypes.POINTER(ZpPair), i32,
                                          vp, vp, vp, ctypes.POINTER(ZpShape), vp, sz, vp]
@@ -228,6 +231,22 @@ def chunk_attn_partial(q, k, v, pairs, part_rows, o_part=None, lse_part=None, sc
                                     arr, n, o_part.data_ptr(), lse_part.data_ptr(), int(part_rows), ctypes.byref(sh),
                                     ws.data_ptr(), ws.numel(), _stream_ptr(stream)))
     return o_part, lse_part
+
+
+def chunk_attn_update(q, k, v, pairs, o_run, lse_run, scale=0.0, ws=None, stream=None):
+    """One ring round merged in place into the running fp32 (o_run [T,Hq,d], lse_run [Hq,T])."""
+    T, Hq, d = q.shape
+    Hkv = k.shape[1]
+    sh = make_shape(T, 0, Hq, Hkv, d, scale)
+    arr, n = _pairs_array(pairs)
+    assert o_run.dtype == torch.float32 and o_run.is_contiguous() and lse_run.dtype == torch.float32 and lse_run.is_contiguous()
+    need = workspace_bytes(FN_PARTIAL, sh, None, n)
+    if ws is None:
+        ws = workspace(need, q.device, "partial")
+    _check(lib().chunk_attn_update(q.data_ptr(), k.data_ptr(), v.data_ptr(), _tok_stride(q), _tok_stride(k), _tok_stride(v),
+                                   arr, n, o_run.data_ptr(), lse_run.data_ptr(), ctypes.byref(sh), ws.data_ptr(),
+                                   ws.numel(), _stream_ptr(stream)))
+    return o_run, lse_run
 
 
 def chunk_attn_partial_bwd(dout, q, k, v, o, lse, pairs, dq_acc, dk_acc, dv_acc, scale=0.0, ws=None, stream=None):

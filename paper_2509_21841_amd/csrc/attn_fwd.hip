@@ -182,18 +182,38 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const float lse = l_tot > 0.f ? (mc * 0.6931471805599453f + __logf(l_tot)) : -INFINITY;
   if (row_ok) {
     const int64_t orow = (int64_t)t.out_row0 + row;
-    if (hi == 0) p.lse[(int64_t)h * p.lse_stride + orow] = lse;
     if (PARTIAL) {
+      // weights of the running row (w_old) and of this partial (w_new, its 1/l folded in); without update: 0 and 1/l
+      float w_old = 0.f, w_new = inv, lse_out = lse;
+      if (p.update) {
+        const float lse_old = p.lse[(int64_t)h * p.lse_stride + orow];
+        const float mx = fmaxf(lse_old, lse);
+        if (mx == -INFINITY) {
+          w_new = 0.f;
+        } else {
+          const float e_old = __expf(lse_old - mx), e_new = __expf(lse - mx);
+          const float tot = e_old + e_new;
+          lse_out = mx + __logf(tot);
+          w_old = e_old / tot;
+          w_new = e_new / tot * inv;
+        }
+      }
+      if (hi == 0) p.lse[(int64_t)h * p.lse_stride + orow] = lse_out;
       float *op = (float *)p.o + orow * p.o_stride + (int64_t)h * D + 4 * hi;
 #pragma unroll
       for (int db = 0; db < D / 32; db++)
 #pragma unroll
         for (int b = 0; b < 4; b++) {
-          f32x4 v4 = {o_acc[db][4 * b] * inv, o_acc[db][4 * b + 1] * inv, o_acc[db][4 * b + 2] * inv,
-                      o_acc[db][4 * b + 3] * inv};
+          f32x4 v4 = {o_acc[db][4 * b] * w_new, o_acc[db][4 * b + 1] * w_new, o_acc[db][4 * b + 2] * w_new,
+                      o_acc[db][4 * b + 3] * w_new};
+          if (w_old > 0.f) {  // a row that has seen no key yet may hold anything
+            const f32x4 old = *(const f32x4 *)(op + db * 32 + b * 8);
+            v4[0] += w_old * old[0]; v4[1] += w_old * old[1]; v4[2] += w_old * old[2]; v4[3] += w_old * old[3];
+          }
           *(f32x4 *)(op + db * 32 + b * 8) = v4;
         }
     } else {
+      if (hi == 0) p.lse[(int64_t)h * p.lse_stride + orow] = lse;
       __bf16 *op = (__bf16 *)p.o + orow * p.o_stride + (int64_t)h * D + 4 * hi;
 #pragma unroll
       for (int db = 0; db < D / 32; db++)

@@ -384,6 +384,65 @@ int chunk_attn_partial(const void *q, const void *k, const void *v, int64_t q_st
   return ZP_OK;
 }
 
+int chunk_attn_update(const void *q, const void *k, const void *v, int64_t q_stride, int64_t k_stride, int64_t v_stride,
+                      const zp_pair *pairs, int32_t n_pairs, float *o_run, float *lse_run, const zp_shape *sh,
+                      void *ws, size_t ws_bytes, void *stream) {
+  int rc = check_shape(sh);
+  if (rc) return rc;
+  if (n_pairs < 0) return ZP_EINVAL;
+  if (n_pairs == 0 || sh->T == 0) return ZP_OK;
+  if (!q || !k || !v || !o_run || !lse_run || !pairs) return ZP_EINVAL;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o_run)) return ZP_EINVAL;
+  if (check_stride(q_stride, sh->Hq, sh->d) || check_stride(k_stride, sh->Hkv, sh->d) ||
+      check_stride(v_stride, sh->Hkv, sh->d))
+    return ZP_EINVAL;
+  // the running rows are read, merged and written back without atomics: a query row may appear in one pair only
+  std::vector<std::pair<int32_t, int32_t>> qr;
+  for (int i = 0; i < n_pairs; i++) {
+    const zp_pair &pr = pairs[i];
+    if (pr.q_len < 0 || pr.k_len < 0 || pr.q_tok0 < 0 || pr.k_tok0 < 0 || pr.q_pos0 < 0 || pr.k_pos0 < 0) return ZP_EINVAL;
+    if ((int64_t)pr.q_tok0 + pr.q_len > sh->T || (int64_t)pr.k_tok0 + pr.k_len > sh->T) return ZP_EINVAL;
+    if (pr.q_len > 0) qr.push_back({pr.q_tok0, pr.q_tok0 + pr.q_len});
+  }
+  std::sort(qr.begin(), qr.end());
+  for (size_t i = 1; i < qr.size(); i++)
+    if (qr[i].first < qr[i - 1].second) return ZP_EINVAL;
+  const int bm = zp_attn_fwd_block_rows(sh->d);
+  std::vector<CostTile> tiles;
+  tiles.reserve((size_t)count_pair_blocks(pairs, n_pairs, bm));
+  for (int i = 0; i < n_pairs; i++) {
+    const zp_pair &pr = pairs[i];
+    for (int32_t r0 = 0; r0 < pr.q_len; r0 += bm) {
+      CostTile c;
+      c.t.q_tok0 = pr.q_tok0 + r0;
+      c.t.q_rows = std::min(bm, pr.q_len - r0);
+      c.t.q_pos0 = pr.q_pos0 + r0;
+      c.t.k_tok0 = pr.k_tok0;
+      c.t.k_len = pr.k_len;
+      c.t.k_pos0 = pr.k_pos0;
+      c.t.out_row0 = c.t.q_tok0;  // the running rows are the query's own token rows
+      c.t.aux = 0;
+      c.cost = tile_cost(c.t);
+      if (c.cost > 0) tiles.push_back(c);  // a block that sees no key leaves its rows as they are
+    }
+  }
+  if (tiles.empty()) return ZP_OK;
+  sort_by_cost(tiles);
+  if ((rc = check_ws(ws, ws_bytes, align256(tiles.size() * sizeof(zp_tile))))) return rc;
+  if ((rc = upload_tiles(tiles, ws, (hipStream_t)stream))) return rc;
+  zp_attn_params p{};
+  p.q = (const __bf16 *)q; p.k = (const __bf16 *)k; p.v = (const __bf16 *)v;
+  p.q_stride = q_stride; p.k_stride = k_stride; p.v_stride = v_stride;
+  p.tiles = (const zp_tile *)ws; p.n_tiles = (int32_t)tiles.size();
+  p.Hq = sh->Hq; p.Hkv = sh->Hkv; p.grp = sh->Hq / sh->Hkv;
+  p.scale = eff_scale(sh); p.scale_log2 = p.scale * 1.4426950408889634f;
+  p.o = o_run; p.o_stride = (int64_t)sh->Hq * sh->d; p.lse = lse_run; p.lse_stride = sh->T;
+  p.update = 1;
+  hipError_t e = (hipError_t)zp_launch_attn_fwd(&p, sh->d, 1, bm, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, "chunk_attn_update launch");
+  return ZP_OK;
+}
+
 int lse_merge(const float *o_part, const float *lse_part, int64_t part_rows, const zp_merge *merges, int32_t n_merges,
               void *o, int64_t o_stride, float *lse, const zp_shape *sh, void *ws, size_t ws_bytes, void *stream) {
   int rc = check_shape(sh);

@@ -40,6 +40,7 @@ struct zp_attn_params {
   int64_t o_stride;  // token stride of o in elements
   float *lse;        // [Hq][lse_stride]
   int64_t lse_stride;
+  int32_t update;    // partial kernel only: merge the result into the running (o, lse) found at the output rows
 };
 
 // blockIdx -> (unit, head-in-group). Workgroups are dealt to the 8 XCDs round-robin by blockIdx, so

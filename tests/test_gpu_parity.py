@@ -182,6 +182,50 @@ def test_partial_rows_without_visible_keys():
     assert np.isneginf(widen(lp)[:, 3:103]).all()
 
 
+@pytest.mark.parametrize("L,C,Hq,Hkv,d", [(1000, 4, 4, 2, 128), (777, 3, 2, 2, 64), (130, 8, 2, 1, 128), (5, 8, 2, 1, 64),
+                                          (2100, 16, 2, 1, 128)])
+def test_rounds_merged_in_place_equal_whole(L, C, Hq, Hkv, d):
+    """chunk_attn_update over the ring rounds: after every round the running rows equal the oracle's partial results
+    merged so far; after the last they equal the whole-sequence attention."""
+    lengths = [50, L, 31]
+    (q, k, v), cu = make(lengths, Hq, Hkv, d, 47)
+    T = q.shape[0]
+    t0 = int(cu[1])
+    pairs, _, _ = B.chunk_pairs(t0, L, C)
+    opairs, _, _ = oracle.causal_pairs(t0, L, C)
+    order = [(qc, kc) for qc in range(C) for kc in range(qc + 1)]
+    by = dict(zip(order, opairs))
+    o_run = torch.full((T, Hq, d), float("nan"), dtype=torch.float32, device=DEV)     # anything: LSE = -inf says "empty"
+    lse_run = torch.full((Hq, T), float("-inf"), dtype=torch.float32, device=DEV)
+    ro = np.zeros((T, Hq, d)); rl = np.full((Hq, T), -np.inf)
+    qw, kw, vw = widen(q), widen(k), widen(v)
+    for rnd, ornd in zip(B.ring_rounds(pairs, C), oracle.ring_rounds(C)):
+        B.chunk_attn_update(q, k, v, rnd, o_run, lse_run)
+        # oracle: this round's partials, then merged with the running rows as one more part
+        plist = []
+        rows = 0
+        for pr in ornd:
+            p = dict(by[pr]); p["out_row0"] = rows; rows += p["q_len"]; plist.append(p)
+        pop, plp = oracle.chunk_attn_partial(qw, kw, vw, plist, rows)
+        for p in plist:
+            n, a, r0 = p["q_len"], p["q_tok0"], p["out_row0"]
+            if n == 0:
+                continue
+            stack_o = np.concatenate([ro[a:a + n], pop[r0:r0 + n]]); stack_l = np.concatenate([rl[:, a:a + n], plp[:, r0:r0 + n]], axis=1)
+            mo, ml = oracle.lse_merge(stack_o, stack_l, [(0, n, [0, n])], n)
+            ro[a:a + n] = mo; rl[:, a:a + n] = ml
+        torch.cuda.synchronize()
+        seen = ~np.isneginf(rl[0])
+        assert_lse_close("running LSE", widen(lse_run), rl)
+        assert_close("running O", widen(o_run)[seen], ro[seen])
+    wo, wl = oracle.varlen_attn_fwd(qw, kw, vw, cu)
+    sl = slice(t0, t0 + L)
+    assert_close("final O", widen(o_run)[sl], wo[sl]); assert_lse_close("final LSE", widen(lse_run)[:, sl], wl[:, sl])
+    assert np.isneginf(widen(lse_run)[:, :t0]).all() and np.isneginf(widen(lse_run)[:, t0 + L:]).all()
+    bits = B.accum_to_bf16(torch.nan_to_num(o_run)).view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(bits, oracle.f32_to_bf16_bits(torch.nan_to_num(o_run).cpu().numpy()))
+
+
 # ---- backward ----------------------------------------------------------------------------------------
 def run_bwd(lengths, Hq, Hkv, d, seed, scale=0.0):
     (q, k, v, do), cu = make(lengths, Hq, Hkv, d, seed, with_dout=True)

@@ -97,6 +97,12 @@ def test_chunked_backward_validation_without_device():
     assert rc([(100, 50, 0, 50)], ws=0) == -3
     assert rc([(100, 50, 0, 50)], wsb=64) == -3
     assert rc([]) == 0                                          # empty round
+    arr = (B.ZpPair * 2)()
+    for n, (qt, ql, kt, kl) in enumerate([(100, 50, 0, 50), (120, 50, 50, 50)]):
+        arr[n].q_tok0, arr[n].q_len, arr[n].k_tok0, arr[n].k_len, arr[n].q_pos0, arr[n].k_pos0 = qt, ql, kt, kl, qt, kt
+    upd = lambda n, o=A: L.chunk_attn_update(A, A, A, 256, 256, 256, arr, n, o, A, ctypes.byref(sh), A, 1 << 22, None)
+    assert upd(2) == -1                                         # two pairs share query rows
+    assert upd(1, o=0) == -1 and upd(0) == 0
     assert L.zp_accum_to_bf16(A, A, 12, None) == -1             # not a multiple of 8 elements
     assert L.zp_accum_to_bf16(0, A, 64, None) == -1
     assert L.zp_accum_to_bf16(A, A, 0, None) == 0
