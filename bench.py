@@ -47,6 +47,12 @@ WORKLOADS = {
     # sequence the Q chunks of its ring rank against their causal KV chunks, merged by LSE
     "rankshare-p8-longtail-128k": dict(T=131072, Hq=32, Hkv=8, d=128, seed=1003, mix="longtail", C=0, bwd=False,
                                        remap=False, rank_share=dict(P=8, N=1, L=20480, device=0)),
+    # the whole 8-device node on one GPU: the partitioner places the long-tail batch (capacity 20480 tokens per device),
+    # device buffers laid end to end are the attention layout, the remap planner's permutation connects it to the
+    # token-balanced layout, local sequences run whole and ring sequences as chunk pairs, one ring round per call
+    # (forward merged in place, backward accumulated in fp32)
+    "node-p8-longtail-128k": dict(T=131072, Hq=32, Hkv=8, d=128, seed=1003, mix="longtail", C=0, bwd=True, remap=True,
+                                  node=dict(P=8, N=1, L=20480)),
 }
 
 
@@ -155,8 +161,48 @@ class Job:
                 B.remap_tokens(self.dv, self.idx, 1, dst=self.dv_lin)
 
 
-def kernel_flops(job: Job, label: str) -> float:
-    """Algorithmic FLOPs one launch of a kernel performs (2 FLOP per multiply-add over unmasked pairs)."""
+class NodeBenchJob:
+    """The emulated-node workload: same interface as Job, built on paper_2509_21841_amd.node."""
+
+    def __init__(self, name, dev):
+        from paper_2509_21841_amd.node import NodeJob, NodePlan
+        w = WORKLOADS[name]
+        self.name, self.w, self.dev = name, w, dev
+        T, Hq, Hkv, d = w["T"], w["Hq"], w["Hkv"], w["d"]
+        lengths, _ = synth.lengths_longtail(T, w["seed"])
+        nd = w["node"]
+        self.plan = NodePlan(lengths, nd["P"], nd["N"], nd["L"], b_intra=1, b_inter=8)
+        self.job = NodeJob(self.plan, Hq, Hkv, d, dev)
+        self.lengths = lengths
+        self.cu = synth.cu_seqlens(lengths)
+        # balanced-layout inputs (what the linear modules hand over); values are i.i.d., so drawing them directly in
+        # that layout is the same distribution as permuting a batch drawn in sequence order
+        self.q_lin, self.k_lin, self.v_lin, self.do_lin = synth.make_qkv(T, Hq, Hkv, d, w["seed"], dev, with_dout=True)
+        e = lambda t: torch.empty_like(t)
+        self.q, self.k, self.v, self.do = e(self.q_lin), e(self.k_lin), e(self.v_lin), e(self.do_lin)
+        self.o_lin, self.dq_lin, self.dk_lin, self.dv_lin = e(self.q_lin), e(self.q_lin), e(self.k_lin), e(self.v_lin)
+        self.n_long = len({s["seq"] for s in self.plan.ring_segments})
+        self.n_pairs = sum(n for _, n in self.plan.rounds)
+        self.pairs_total = self.plan.ring_pairs + self.plan.local_pairs
+        self.pairs_long = self.plan.ring_pairs
+        self.flops_fwd = 4 * d * Hq * self.pairs_total
+        self.flops_bwd = 10 * d * Hq * self.pairs_total
+        self.merge_bytes = 0
+        rb = lambda t: 2 * t.numel() * 2 + 4 * T
+        self.remap_bytes = 4 * rb(self.q) + 4 * rb(self.k)
+
+    def step(self):
+        j = self.job
+        j.to_attention(self.q_lin, self.q); j.to_attention(self.k_lin, self.k); j.to_attention(self.v_lin, self.v)
+        o, _ = j.forward(self.q, self.k, self.v)
+        j.to_balanced(o, self.o_lin)
+        j.to_attention(self.do_lin, self.do)
+        dq, dk, dv = j.backward(self.do, self.q, self.k, self.v)
+        j.to_balanced(dq, self.dq_lin); j.to_balanced(dk, self.dk_lin); j.to_balanced(dv, self.dv_lin)
+
+
+def kernel_flops(job, label: str) -> float:
+    """Algorithmic FLOPs one step spends in a kernel (2 FLOP per multiply-add over unmasked pairs)."""
     d, Hq = job.w["d"], job.w["Hq"]
     per_gemm_all = 2 * d * Hq * job.pairs_total
     per_gemm_long = 2 * d * Hq * job.pairs_long
@@ -225,7 +271,7 @@ def main():
     ap.add_argument("--workload", default="longtail-128k-gqa32x8", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     a = ap.parse_args()
-    if WORKLOADS[a.workload].get("rank_share") or not WORKLOADS[a.workload]["bwd"]:
+    if WORKLOADS[a.workload].get("rank_share") or WORKLOADS[a.workload].get("node") or not WORKLOADS[a.workload]["bwd"]:
         a.no_cpu_baseline = True   # the oracle sample is defined for the forward+backward workloads
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -236,7 +282,7 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     B.lib()
-    job = Job(a.workload, dev)
+    job = NodeBenchJob(a.workload, dev) if WORKLOADS[a.workload].get("node") else Job(a.workload, dev)
     for _ in range(a.warmup):
         job.step()
     torch.cuda.synchronize()
@@ -263,7 +309,7 @@ def main():
             for k, v in by.items()}
     attn = {k: v for k, v in kern.items() if k.startswith("attn")}
     dom = max(attn, key=lambda k: attn[k]["ms_per_step"])
-    ach = kernel_flops(job, dom) / (kern[dom]["avg_ms"] * 1e-3) / 1e12
+    ach = kernel_flops(job, dom) / (kern[dom]["ms_per_step"] * 1e-3) / 1e12
     roofline = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": MEASURED_TRAFFIC_BYTES.get((a.workload, dom)),
                 "mfma_sustained_tflops": sustained,
@@ -276,10 +322,12 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": a.workload, "T": job.w["T"], "Hq": job.w["Hq"], "Hkv": job.w["Hkv"], "head_dim": job.w["d"],
                    "n_sequences": len(job.lengths), "max_len": max(job.lengths), "n_long_chunked": job.n_long,
-                   "chunks": job.w["C"], "stages": ",".join(
-                       (["remap"] if job.w["remap"] else []) + ["fwd"] + (["chunk_partial", "lse_merge"] if job.n_pairs else [])
+                   "chunks": job.w["C"] or (job.plan.max_chunks if hasattr(job, "plan") else 0), "stages": ",".join(
+                       (["remap"] if job.w["remap"] else []) + ["fwd"]
+                       + (["chunk_update_rounds"] if hasattr(job, "plan") else ["chunk_partial", "lse_merge"] if job.n_pairs else [])
                        + (["remap_inv"] if job.w["remap"] else [])
-                       + ((["remap"] if job.w["remap"] else []) + ["bwd"] + (["remap_inv"] if job.w["remap"] else [])
+                       + ((["remap"] if job.w["remap"] else []) + ["bwd"] + (["chunk_bwd_rounds"] if hasattr(job, "plan") else [])
+                          + (["remap_inv"] if job.w["remap"] else [])
                           if job.w["bwd"] else []))},
         "frac_of_mfma_peak": value / MFMA_BF16_PEAK_TFLOPS,
         "roofline": roofline,

@@ -88,11 +88,13 @@ int varlen_attn_fwd(const void *q, const void *k, const void *v, int64_t q_strid
  *   dQ_i = scale sum_{j<=i} dS_ij k_j ;  dK_j = scale sum_{h in group} sum_{i>=j} dS_ij q_i ;
  *   dV_j = sum_{h in group} sum_{i>=j} P_ij dO_i.
  * Deterministic (no atomics): one kernel owns key/value rows, one owns query rows.
+ * seq_skip_host: NULL, or host [S] flags; the dQ/dK/dV rows of a flagged sequence are not written (the caller runs
+ * it as chunk pairs with chunk_attn_partial_bwd instead).
  * dq/dk/dv token strides are dq_stride (= for dQ) and dkv_stride (for dK and dV). */
 int varlen_attn_bwd(const void *dout, const void *q, const void *k, const void *v, const void *o, const float *lse,
                     int64_t do_stride, int64_t q_stride, int64_t k_stride, int64_t v_stride, int64_t o_stride,
-                    const int32_t *cu_seqlens_host, void *dq, void *dk, void *dv, int64_t dq_stride,
-                    int64_t dkv_stride, const zp_shape *sh, void *ws, size_t ws_bytes, void *stream);
+                    const int32_t *cu_seqlens_host, const uint8_t *seq_skip_host, void *dq, void *dk, void *dv,
+                    int64_t dq_stride, int64_t dkv_stride, const zp_shape *sh, void *ws, size_t ws_bytes, void *stream);
 
 /* Partial attention of (Q chunk, KV chunk) pairs (Sec. 3.2, the per-round compute of ring attention):
  * for each pair and head, softmax over only that KV chunk's causally visible keys, normalised by its
@@ -175,6 +177,18 @@ typedef struct {
  * every node to s0_final[N] (both optional). Returns ZP_EWORKSPACE if max_out was too small (*n_out = needed). */
 int zp_partition(const int32_t *lengths, int32_t S, int32_t P, int32_t N, int32_t L, zp_placement *out,
                  int32_t max_out, int32_t *n_out, int32_t *s1_final, int32_t *s0_final);
+
+/* Host helper: the attention layout a placement list implies (Sec. 3.1, 3.2), as runs of consecutive tokens of the
+ * concatenated device buffers: devices in (node, device) order, on each its placements in list order; a whole
+ * sequence is one run, ring rank r of G the two runs chunk r and chunk 2G-1-r of 2G equal-length chunks.
+ * tok0 = first token of the run in the concatenation, pos0 = its first position inside its sequence.
+ * Writes up to max_out runs, the count to *n_out and (optional) the tokens of every device to tokens_per_rank[N*P],
+ * which is the vector A of the remap planner. Returns ZP_EWORKSPACE if max_out was too small (*n_out = needed). */
+typedef struct {
+  int32_t seq, chunk, n_chunks, pos0, len, tok0, node, device;
+} zp_segment;
+int zp_node_segments(const int32_t *lengths, int32_t S, const zp_placement *placements, int32_t n_placements, int32_t P,
+                     int32_t N, zp_segment *out, int32_t max_out, int32_t *n_out, int32_t *tokens_per_rank);
 
 /* Host helper: transfer plan of the remapping layer (Sec. 3.4, Eq. 2). A[d]: tokens per rank in the attention layout;
  * rank r sits in node r / P. The balanced target is B_i = floor(T/d) + (i < T mod d). Writes M[d*d] (row-major,

@@ -62,7 +62,7 @@ def lib() -> ctypes.CDLL:
     L.varlen_attn_fwd.restype = ctypes.c_int
     L.varlen_attn_fwd.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp, vp, i64, vp, ctypes.POINTER(ZpShape), vp, sz, vp]
     L.varlen_attn_bwd.restype = ctypes.c_int
-    L.varlen_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, vp, vp, vp, vp, i64, i64,
+    L.varlen_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, vp, vp, vp, vp, vp, i64, i64,
                                   ctypes.POINTER(ZpShape), vp, sz, vp]
     L.chunk_attn_partial.restype = ctypes.c_int
     L.chunk_attn_partial.argtypes = [vp, vp, vp, i64, i64, i64, ctypes.POINTER(ZpPair), i32, vp, vp, i64,
@@ -166,8 +166,9 @@ def varlen_attn_fwd(q, k, v, cu_seqlens, o=None, lse=None, scale=0.0, ws=None, s
     return o, lse
 
 
-def varlen_attn_bwd(dout, q, k, v, o, lse, cu_seqlens, dq=None, dk=None, dv=None, scale=0.0, ws=None, stream=None):
-    """-> (dq [T,Hq,d], dk [T,Hkv,d], dv [T,Hkv,d]) bf16."""
+def varlen_attn_bwd(dout, q, k, v, o, lse, cu_seqlens, dq=None, dk=None, dv=None, scale=0.0, ws=None, stream=None,
+                    seq_skip=None):
+    """-> (dq [T,Hq,d], dk [T,Hkv,d], dv [T,Hkv,d]) bf16. Rows of sequences flagged in seq_skip are not written."""
     cu = _cu_host(cu_seqlens)
     T, Hq, d = q.shape
     Hkv = k.shape[1]
@@ -179,15 +180,21 @@ def varlen_attn_bwd(dout, q, k, v, o, lse, cu_seqlens, dq=None, dk=None, dv=None
     if ws is None:
         ws = workspace(need, q.device, "bwd")
     assert _tok_stride(dk) == _tok_stride(dv)
+    skip = None if seq_skip is None else np.ascontiguousarray(seq_skip, dtype=np.uint8)
+    assert skip is None or len(skip) == len(cu) - 1
     _check(lib().varlen_attn_bwd(dout.data_ptr(), q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
                                  _tok_stride(dout), _tok_stride(q), _tok_stride(k), _tok_stride(v), _tok_stride(o),
-                                 cu.ctypes.data_as(ctypes.c_void_p), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(),
+                                 cu.ctypes.data_as(ctypes.c_void_p),
+                                 None if skip is None else skip.ctypes.data_as(ctypes.c_void_p),
+                                 dq.data_ptr(), dk.data_ptr(), dv.data_ptr(),
                                  _tok_stride(dq), _tok_stride(dk), ctypes.byref(sh), ws.data_ptr(), ws.numel(),
                                  _stream_ptr(stream)))
     return dq, dk, dv
 
 
 def _pairs_array(pairs):
+    if isinstance(pairs, tuple) and len(pairs) == 2 and isinstance(pairs[0], ctypes.Array):
+        return pairs                      # (array, count) prepared earlier
     if isinstance(pairs, ctypes.Array):
         return pairs, len(pairs)
     arr = (ZpPair * max(len(pairs), 1))()
@@ -374,6 +381,28 @@ def remap_indices(A, M):
     _check(lib().zp_remap_indices(A.ctypes.data_as(ctypes.c_void_p), M.ctypes.data_as(ctypes.c_void_p), len(A),
                                   idx.ctypes.data_as(ctypes.c_void_p), len(idx)))
     return idx
+
+
+class ZpSegment(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("seq", "chunk", "n_chunks", "pos0", "len", "tok0", "node", "device")]
+
+
+def node_segments(lengths, placements, P: int, N: int):
+    """Host helper: attention layout of a placement list -> (runs as dicts, tokens per device)."""
+    lens = np.ascontiguousarray(lengths, dtype=np.int32)
+    arr = (ZpPlacement * max(len(placements), 1))()
+    for i, pl in enumerate(placements):
+        for f, _ in ZpPlacement._fields_:
+            setattr(arr[i], f, int(pl[f]))
+    cap = 2 * len(placements) + 1
+    out = (ZpSegment * cap)()
+    n = ctypes.c_int32(0)
+    A = np.zeros(P * N, np.int32)
+    lib().zp_node_segments.restype = ctypes.c_int
+    _check(lib().zp_node_segments(lens.ctypes.data_as(ctypes.c_void_p), len(lens), arr, len(placements), int(P), int(N),
+                                  out, cap, ctypes.byref(n), A.ctypes.data_as(ctypes.c_void_p)))
+    segs = [{f: getattr(out[i], f) for f, _ in ZpSegment._fields_} for i in range(n.value)]
+    return segs, A
 
 
 def partition(lengths, P: int, N: int, L: int):

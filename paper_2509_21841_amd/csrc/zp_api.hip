@@ -540,9 +540,9 @@ int zp_chunk_pairs(int32_t tok0, int32_t L, int32_t C, int32_t rank, int32_t row
 
 extern "C" int varlen_attn_bwd(const void *dout, const void *q, const void *k, const void *v, const void *o,
                                const float *lse, int64_t do_stride, int64_t q_stride, int64_t k_stride,
-                               int64_t v_stride, int64_t o_stride, const int32_t *cu, void *dq, void *dk, void *dv,
-                               int64_t dq_stride, int64_t dkv_stride, const zp_shape *sh, void *ws, size_t ws_bytes,
-                               void *stream) {
+                               int64_t v_stride, int64_t o_stride, const int32_t *cu, const uint8_t *seq_skip,
+                               void *dq, void *dk, void *dv, int64_t dq_stride, int64_t dkv_stride,
+                               const zp_shape *sh, void *ws, size_t ws_bytes, void *stream) {
   int rc = check_shape(sh);
   if (rc) return rc;
   if ((rc = check_cu(cu, sh))) return rc;
@@ -559,7 +559,7 @@ extern "C" int varlen_attn_bwd(const void *dout, const void *q, const void *k, c
   const int bmq = zp_attn_bwd_block_rows(sh->d, 0), bnk = zp_attn_bwd_block_rows(sh->d, 1);
   std::vector<CostTile> qt, kt;
   qt.reserve((size_t)count_blocks(cu, sh->S, bmq));
-  plan_whole(cu, sh->S, bmq, qt);
+  plan_whole(cu, sh->S, bmq, qt, seq_skip);
   kt.reserve((size_t)count_blocks(cu, sh->S, bnk));
   // Key-block tiles go sequence by sequence, longest sequence first, blocks in position order (descending
   // cost inside the sequence): workgroups that run side by side then walk the same Q/dO rows a few tiles
@@ -569,6 +569,7 @@ extern "C" int varlen_attn_bwd(const void *dout, const void *q, const void *k, c
   std::stable_sort(seq_order.begin(), seq_order.end(),
                    [&](int a, int b) { return cu[a + 1] - cu[a] > cu[b + 1] - cu[b]; });
   for (int s : seq_order) {
+    if (seq_skip && seq_skip[s]) continue;
     const int32_t L = cu[s + 1] - cu[s];
     for (int32_t j0 = 0; j0 < L; j0 += bnk) {
       CostTile c;
@@ -584,6 +585,7 @@ extern "C" int varlen_attn_bwd(const void *dout, const void *q, const void *k, c
       kt.push_back(c);
     }
   }
+  if (qt.empty() && kt.empty()) return ZP_OK;
   const size_t tile_bytes = align256((qt.size() + kt.size()) * sizeof(zp_tile));
   const size_t dvec_bytes = align256((size_t)sh->Hq * (size_t)sh->T * sizeof(float));
   if ((rc = check_ws(ws, ws_bytes, tile_bytes + 2 * dvec_bytes))) return rc;

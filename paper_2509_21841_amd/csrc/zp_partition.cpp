@@ -152,3 +152,46 @@ extern "C" int zp_partition(const int32_t *lengths, int32_t S, int32_t P, int32_
   *n_out = n_written;
   return n_written > max_out ? ZP_EWORKSPACE : ZP_OK;
 }
+
+// The attention layout that a placement list implies, as runs of consecutive tokens: devices in (node, device) order,
+// on each device its placements in list order, a whole sequence as one run and ring rank r of G as the two runs
+// chunk r and chunk 2G-1-r (Sec. 3.2).
+extern "C" int zp_node_segments(const int32_t *lengths, int32_t S, const zp_placement *pl, int32_t n_pl, int32_t P,
+                                int32_t N, zp_segment *out, int32_t max_out, int32_t *n_out, int32_t *tokens_per_rank) {
+  if (!lengths || !pl || !out || !n_out || S < 0 || n_pl < 0 || P < 1 || N < 1) return ZP_EINVAL;
+  for (int i = 0; i < n_pl; i++) {
+    const zp_placement &x = pl[i];
+    if (x.seq < 0 || x.seq >= S || x.node < 0 || x.node >= N || x.device < 0 || x.device >= P || x.ring < 1 ||
+        x.rank < 0 || x.rank >= x.ring || lengths[x.seq] < 0)
+      return ZP_EINVAL;
+  }
+  int32_t n = 0;
+  int64_t tok = 0;
+  for (int node = 0; node < N; node++)
+    for (int dev = 0; dev < P; dev++) {
+      const int64_t tok_rank0 = tok;
+      for (int i = 0; i < n_pl; i++) {
+        const zp_placement &x = pl[i];
+        if (x.node != node || x.device != dev) continue;
+        const int64_t len = lengths[x.seq], G = x.ring;
+        const int n_runs = G == 1 ? 1 : 2;
+        for (int k = 0; k < n_runs; k++) {
+          const int64_t c = G == 1 ? 0 : (k == 0 ? x.rank : 2 * G - 1 - x.rank);
+          const int64_t C = G == 1 ? 1 : 2 * G;
+          const int64_t p0 = c * len / C, p1 = (c + 1) * len / C;
+          if (n < max_out) {
+            zp_segment &sg = out[n];
+            sg.seq = x.seq; sg.chunk = (int32_t)c; sg.n_chunks = (int32_t)C;
+            sg.pos0 = (int32_t)p0; sg.len = (int32_t)(p1 - p0); sg.tok0 = (int32_t)tok;
+            sg.node = node; sg.device = dev;
+          }
+          n++;
+          tok += p1 - p0;
+        }
+      }
+      if (tok > INT32_MAX) return ZP_EINVAL;
+      if (tokens_per_rank) tokens_per_rank[node * P + dev] = (int32_t)(tok - tok_rank0);
+    }
+  *n_out = n;
+  return n > max_out ? ZP_EWORKSPACE : ZP_OK;
+}

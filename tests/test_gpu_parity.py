@@ -315,3 +315,35 @@ def test_mfma_probe_runs_and_is_deterministic():
     torch.cuda.synchronize()
     assert torch.isfinite(a).all() and torch.equal(a, b) and a.abs().max() > 0
     assert not B.mfma_probe(50, False).any()
+
+
+# ---- a whole node's placement on one GPU ----------------------------------------------------------------
+@pytest.mark.parametrize("lengths,P,N,L,Hq,Hkv,d", [
+    ([700, 90, 300, 1500, 64, 200, 33], 4, 1, 800, 4, 2, 128),       # one intra-node ring, local sequences
+    ([2600, 150, 400, 90, 1100, 60], 2, 2, 700, 2, 1, 64),           # an inter-node ring over both nodes
+    ([100, 200, 50], 4, 1, 400, 2, 2, 64)])                          # everything local
+def test_node_placement_end_to_end(lengths, P, N, L, Hq, Hkv, d):
+    """Partitioner -> attention layout -> remap plan -> engine, against the oracle's whole-sequence attention of the
+    batch as drawn: inputs arrive in the token-balanced layout, outputs are compared there too."""
+    from paper_2509_21841_amd.node import NodeJob, NodePlan
+    plan = NodePlan(lengths, P, N, L, b_intra=1, b_inter=5)
+    T = plan.T
+    (q0, k0, v0, do0), cu0 = make(lengths, Hq, Hkv, d, 53, with_dout=True)      # the batch as drawn
+    to_bal = torch.from_numpy(plan.orig[plan.idx]).to(DEV)                      # balanced position -> drawn position
+    qb, kb, vb, dob = (x[to_bal].contiguous() for x in (q0, k0, v0, do0))       # what the linear modules hand over
+    job = NodeJob(plan, Hq, Hkv, d, DEV)
+    qa, ka, va, doa = (job.to_attention(x) for x in (qb, kb, vb, dob))
+    assert torch.equal(qa.view(torch.int16), q0[torch.from_numpy(plan.orig).to(DEV)].view(torch.int16))
+    o, _ = job.forward(qa, ka, va)
+    ob = job.to_balanced(o)
+    dq, dk, dv = job.backward(doa, qa, ka, va)
+    dqb, dkb, dvb = (job.to_balanced(x) for x in (dq, dk, dv))
+    torch.cuda.synchronize()
+    ro, _ = oracle.varlen_attn_fwd(widen(q0), widen(k0), widen(v0), cu0)
+    rdq, rdk, rdv = oracle.varlen_attn_bwd(widen(do0), widen(q0), widen(k0), widen(v0), cu0)
+    sel = plan.orig[plan.idx]
+    assert_close("O", widen(ob), ro[sel]); assert_close("dQ", widen(dqb), rdq[sel])
+    assert_close("dK", widen(dkb), rdk[sel]); assert_close("dV", widen(dvb), rdv[sel])
+    # the balanced layout gives every rank its target share
+    from oracle import remap_planner as RP
+    assert [int(x) for x in np.asarray(plan.M).sum(axis=1)] == RP.surplus_deficit(plan.A)[0]

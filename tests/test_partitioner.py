@@ -108,3 +108,48 @@ def test_paper_sized_batches():
         pl, s1, s0 = opt.partition(lengths, P, N, L)
         check_properties(lengths, P, N, L, pl, s1, s0)
         assert canon(B.partition(lengths, P, N, L)[0]) == canon(pl)
+
+
+# ---- placement -> attention layout -> remap plan (host composition, no device) -------------------------
+@pytest.mark.parametrize("lengths,P,N,L", [([700, 90, 300, 1500, 64, 200, 33], 4, 1, 800),
+                                           ([2600, 150, 400, 90, 1100, 60], 2, 2, 700),
+                                           ([100, 200, 50], 4, 1, 400), ([5000], 8, 1, 1000)])
+def test_node_plan_composition(lengths, P, N, L):
+    from paper_2509_21841_amd.node import NodePlan
+    from paper_2509_21841_amd import binding as B
+    plan = NodePlan(lengths, P, N, L, b_intra=1, b_inter=4)
+    T = sum(lengths)
+    # runs tile the concatenated device buffers, device by device, and cover every token of every sequence once
+    assert plan.T == T and int(plan.cu[-1]) == T
+    assert sorted(plan.orig.tolist()) == list(range(T)) and sorted(plan.idx.tolist()) == list(range(T))
+    tok = 0
+    for s in plan.segments:
+        assert s["tok0"] == tok and s["len"] >= 0
+        tok += s["len"]
+    per_rank = np.zeros(P * N, np.int64)
+    for s in plan.segments:
+        per_rank[s["node"] * P + s["device"]] += s["len"]
+    assert np.array_equal(per_rank, plan.A)
+    # a ring rank of G holds chunks r and 2G-1-r: the oracle's ring ownership
+    by = {}
+    for s in plan.segments:
+        if s["n_chunks"] > 1:
+            by.setdefault((s["seq"], s["node"], s["device"]), []).append(s["chunk"])
+    for (seq, _, _), chunks in by.items():
+        C = [s for s in plan.segments if s["seq"] == seq][0]["n_chunks"]
+        assert sorted(chunks) == sorted([min(chunks), C - 1 - min(chunks)])
+    # within a round no query run and no key run appears twice; over the rounds every causal chunk pair appears once
+    seen = set()
+    for arr, n in plan.rounds:
+        qs = [(arr[i].q_tok0, arr[i].q_len) for i in range(n) if arr[i].q_len]
+        ks = [(arr[i].k_tok0, arr[i].k_len) for i in range(n) if arr[i].k_len]
+        assert len(set(qs)) == len(qs) and len(set(ks)) == len(ks)
+        for i in range(n):
+            key = (arr[i].q_tok0, arr[i].k_tok0, arr[i].q_pos0, arr[i].k_pos0)
+            assert key not in seen and arr[i].k_pos0 <= arr[i].q_pos0
+            seen.add(key)
+    n_ring = {}
+    for s in plan.segments:
+        if s["n_chunks"] > 1:
+            n_ring[s["seq"]] = s["n_chunks"]
+    assert len(seen) == sum(C * (C + 1) // 2 for C in n_ring.values())
