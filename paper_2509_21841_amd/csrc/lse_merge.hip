@@ -18,6 +18,9 @@ namespace {
 constexpr int MERGE_NT = 512;
 constexpr int MERGE_ROWS = 8;
 
+// MAXP: compile-time bound of n_parts for this launch (the host picks the smallest of 4, 8, 16 that covers every
+// merge), so that the register arrays and the unrolled loops are no larger than needed.
+template <int MAXP>
 __global__ __launch_bounds__(MERGE_NT) void lse_merge_kernel(const float *__restrict__ o_part, const float *__restrict__ lse_part,
                                                              int64_t part_rows, const zp_merge_dev *__restrict__ merges,
                                                              const zp_merge_item *__restrict__ items, int Hq, int d,
@@ -35,28 +38,28 @@ __global__ __launch_bounds__(MERGE_NT) void lse_merge_kernel(const float *__rest
     const int h = rem / d4, c4 = rem - h * d4;
     const int rr = it.row0 + r;
     // all loads of the item are issued before any arithmetic: n_parts LSEs and n_parts float4 in flight
-    float lp[ZP_MAX_PARTS];
-    f32x4 v[ZP_MAX_PARTS];
+    float lp[MAXP];
+    f32x4 v[MAXP];
 #pragma unroll
-    for (int p = 0; p < ZP_MAX_PARTS; p++)
+    for (int p = 0; p < MAXP; p++)
       if (p < mg.n_parts) {
         lp[p] = lse_part[(int64_t)h * part_rows + mg.part_row0[p] + rr];
         v[p] = __builtin_nontemporal_load((const f32x4 *)(o_part + ((int64_t)(mg.part_row0[p] + rr) * Hq + h) * d) + c4);
       }
     float mx = -INFINITY;
 #pragma unroll
-    for (int p = 0; p < ZP_MAX_PARTS; p++)
+    for (int p = 0; p < MAXP; p++)
       if (p < mg.n_parts) mx = fmaxf(mx, lp[p]);
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     float L = -INFINITY;
     if (mx != -INFINITY) {
       float sum = 0.f;
 #pragma unroll
-      for (int p = 0; p < ZP_MAX_PARTS; p++)
+      for (int p = 0; p < MAXP; p++)
         if (p < mg.n_parts) sum += __expf(lp[p] - mx);
       L = mx + __logf(sum);
 #pragma unroll
-      for (int p = 0; p < ZP_MAX_PARTS; p++)
+      for (int p = 0; p < MAXP; p++)
         if (p < mg.n_parts && lp[p] != -INFINITY) acc += __expf(lp[p] - L) * v[p];
     }
     const int64_t t = (int64_t)mg.out_tok0 + rr;
@@ -95,12 +98,17 @@ extern "C" int zp_merge_rows_per_item(void) { return MERGE_ROWS; }
 
 extern "C" int zp_launch_lse_merge(const float *o_part, const float *lse_part, int64_t part_rows, const void *merges_dev,
                                    const void *items_dev, int n_items, int Hq, int d, void *o, int64_t o_stride,
-                                   float *lse, int64_t T, hipStream_t stream) {
+                                   float *lse, int64_t T, int max_parts, hipStream_t stream) {
   if (n_items == 0) return 0;
   zp_prof_begin("lse_merge", stream);
-  hipLaunchKernelGGL(lse_merge_kernel, dim3(n_items), dim3(MERGE_NT), 0, stream, o_part, lse_part, part_rows,
-                     (const zp_merge_dev *)merges_dev, (const zp_merge_item *)items_dev, Hq, d, (__bf16 *)o, o_stride,
-                     lse, T);
+#define ZP_MERGE_LAUNCH(MAXP)                                                                                      \
+  hipLaunchKernelGGL(lse_merge_kernel<MAXP>, dim3(n_items), dim3(MERGE_NT), 0, stream, o_part, lse_part, part_rows, \
+                     (const zp_merge_dev *)merges_dev, (const zp_merge_item *)items_dev, Hq, d, (__bf16 *)o, o_stride, \
+                     lse, T)
+  if (max_parts <= 4) ZP_MERGE_LAUNCH(4);
+  else if (max_parts <= 8) ZP_MERGE_LAUNCH(8);
+  else ZP_MERGE_LAUNCH(16);
+#undef ZP_MERGE_LAUNCH
   zp_prof_end(stream);
   return (int)hipGetLastError();
 }

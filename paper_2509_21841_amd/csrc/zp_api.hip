@@ -21,7 +21,7 @@ int zp_launch_remap(const void *src, void *dst, int64_t row_bytes, const int32_t
 int zp_merge_rows_per_item(void);
 int zp_launch_lse_merge(const float *o_part, const float *lse_part, int64_t part_rows, const void *merges_dev,
                         const void *items_dev, int n_items, int Hq, int d, void *o, int64_t o_stride, float *lse,
-                        int64_t T, hipStream_t stream);
+                        int64_t T, int max_parts, hipStream_t stream);
 struct zp_bwd_params {
   const __bf16 *q, *k, *v, *o, *dout;
   int64_t q_stride, k_stride, v_stride, o_stride, do_stride;
@@ -481,8 +481,10 @@ int lse_merge(const float *o_part, const float *lse_part, int64_t part_rows, con
     }
   rc = pool_upload(slot, ws, desc_bytes + item_bytes, (hipStream_t)stream);
   if (rc) { pool_release_unused(slot); return rc; }
+  int max_parts = 1;
+  for (int i = 0; i < n_merges; i++) max_parts = std::max(max_parts, (int)merges[i].n_parts);
   hipError_t e = (hipError_t)zp_launch_lse_merge(o_part, lse_part, part_rows, ws, (char *)ws + desc_bytes, (int)n_items,
-                                                 sh->Hq, sh->d, o, o_stride, lse, sh->T, (hipStream_t)stream);
+                                                 sh->Hq, sh->d, o, o_stride, lse, sh->T, max_parts, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e, "lse_merge launch");
   return ZP_OK;
 }
