@@ -6,6 +6,7 @@
 // Both recompute P from the forward's LSE. In each kernel the accumulator of the first two products already
 // has the register layout the third/fourth product needs as its B operand; the transposed A operands
 // (K^T, Q^T, dO^T) come from the row-major LDS tiles through the transposing LDS read.
+#include <type_traits>
 #include "zp_common.h"
 
 struct zp_bwd_params {
@@ -87,13 +88,16 @@ __device__ __forceinline__ void add_acc_rows(float *dst, const f32x16 (&acc)[D /
 template <int D, bool MASK>
 __device__ __forceinline__ void dq_half(const char *Kb, const char *Vb, int kb, const bf16x8 (&qreg)[D / 16],
                                         const bf16x8 (&doreg)[D / 16], f32x16 (&dq_acc)[D / 32], float c_log2,
-                                        float lse2, float Dq, int j0, int hi, int nvis_lane,
+                                        float lse2, const f32x16 &negD, int j0, int hi, int nvis_lane,
                                         const zp_lds_offsets<D> &lo) {
   constexpr int KK = D / 16, DB = D / 32;
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  f32x16 s = zero, dp = zero;
+  // the dP^T chain starts from -D (a lane holds one query, so the seed is the same in all 16 registers and lives in
+  // registers for the whole kernel): the accumulator then holds dP - D
+  f32x16 s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo.rows(Kb, kb, 0), qreg[0], zero, 0, 0, 0);
+  f32x16 dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo.rows(Vb, kb, 0), doreg[0], negD, 0, 0, 0);
 #pragma unroll
-  for (int kk = 0; kk < KK; kk++) {
+  for (int kk = 1; kk < KK; kk++) {
     s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo.rows(Kb, kb, kk), qreg[kk], s, 0, 0, 0);
     dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo.rows(Vb, kb, kk), doreg[kk], dp, 0, 0, 0);
   }
@@ -114,7 +118,7 @@ __device__ __forceinline__ void dq_half(const char *Kb, const char *Vb, int kb, 
       const int j = j0 + kb * 32 + 8 * (r >> 2) + 4 * hi + (r & 3);
       if (j >= nvis_lane) pv = 0.f;
     }
-    dsb[r >> 3][r & 7] = (__bf16)(pv * (dp[r] - Dq));
+    dsb[r >> 3][r & 7] = (__bf16)(pv * dp[r]);
   }
 #pragma unroll
   for (int m = 0; m < 2; m++)
@@ -207,10 +211,14 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
   zp_wait_async();
   __syncthreads();
 
-  for (int it = 0; it < n_kt; it++) {
-    const int j0 = it * 64, buf = it & 1;
-    const bool more = it + 1 < n_kt;
-    if (more) {
+  f32x16 negD;
+#pragma unroll
+  for (int r = 0; r < 16; r++) negD[r] = -Dq;
+  // one key tile out of LDS buffer BUF (compile-time, so that every LDS address is a register plus an immediate)
+  auto key_tile = [&](int it, auto BUF) {
+    constexpr int buf = decltype(BUF)::value;
+    const int j0 = it * 64;
+    if (it + 1 < n_kt) {
       kst.issue(Ks + (buf ^ 1) * TILEB, j0 + 64, t.k_len);
       vst.issue(Vs + (buf ^ 1) * TILEB, j0 + 64, t.k_len);
     }
@@ -218,15 +226,19 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
       const char *Kb = Ks + buf * TILEB;
       const char *Vb = Vs + buf * TILEB;
       if (j0 + 64 > nvis_w_min) {
-        dq_half<D, true>(Kb, Vb, 0, qreg, doreg, dq_acc, c_log2, lse2, Dq, j0, hi, nvis_lane, lo);
-        dq_half<D, true>(Kb, Vb, 1, qreg, doreg, dq_acc, c_log2, lse2, Dq, j0, hi, nvis_lane, lo);
+        dq_half<D, true>(Kb, Vb, 0, qreg, doreg, dq_acc, c_log2, lse2, negD, j0, hi, nvis_lane, lo);
+        dq_half<D, true>(Kb, Vb, 1, qreg, doreg, dq_acc, c_log2, lse2, negD, j0, hi, nvis_lane, lo);
       } else {
-        dq_half<D, false>(Kb, Vb, 0, qreg, doreg, dq_acc, c_log2, lse2, Dq, j0, hi, nvis_lane, lo);
-        dq_half<D, false>(Kb, Vb, 1, qreg, doreg, dq_acc, c_log2, lse2, Dq, j0, hi, nvis_lane, lo);
+        dq_half<D, false>(Kb, Vb, 0, qreg, doreg, dq_acc, c_log2, lse2, negD, j0, hi, nvis_lane, lo);
+        dq_half<D, false>(Kb, Vb, 1, qreg, doreg, dq_acc, c_log2, lse2, negD, j0, hi, nvis_lane, lo);
       }
     }
     zp_wait_async();
     __syncthreads();
+  };
+  for (int it = 0; it < n_kt; it += 2) {
+    key_tile(it, std::integral_constant<int, 0>{});
+    if (it + 1 < n_kt) key_tile(it + 1, std::integral_constant<int, 1>{});
   }
 
   if (row_ok) {
