@@ -29,28 +29,6 @@ namespace {
 constexpr int BWD_NT = 256;
 constexpr float LOG2E = 1.4426950408889634f;
 
-// cooperative global -> register -> LDS staging of a [64][D] bf16 tile (zp_swz layout)
-template <int D>
-struct TileStage {
-  static constexpr int CPT = 64 * D / 8 / BWD_NT;  // 16-byte chunks per thread
-  u32x4 r[CPT];
-  __device__ __forceinline__ void load(const __bf16 *base, int64_t stride, int row0, int rows_total, int tid) {
-#pragma unroll
-    for (int n = 0; n < CPT; n++) {
-      int id = tid + n * BWD_NT, rr = id / (D / 8), c = id % (D / 8);
-      if (row0 + rr < rows_total) r[n] = *(const u32x4 *)(base + (int64_t)(row0 + rr) * stride + c * 8);
-      else r[n] = u32x4{0, 0, 0, 0};
-    }
-  }
-  __device__ __forceinline__ void store(char *lds, int tid) const {
-#pragma unroll
-    for (int n = 0; n < CPT; n++) {
-      int id = tid + n * BWD_NT, rr = id / (D / 8), c = id % (D / 8);
-      zp_lds_write16(lds, zp_swz<D>(rr, c), r[n]);
-    }
-  }
-};
-
 template <int D>
 __device__ __forceinline__ void store_acc_rows(__bf16 *dst, const f32x16 (&acc)[D / 32], float mul) {
 #pragma unroll

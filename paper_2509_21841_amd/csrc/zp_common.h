@@ -70,12 +70,9 @@ __device__ __forceinline__ float zp_pair_sum(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-// 16-byte LDS read / write and the gfx950 transposing 8-byte LDS read.
+// 16-byte LDS read and the gfx950 transposing 8-byte LDS read.
 __device__ __forceinline__ bf16x8 zp_lds_read16(const char *smem, int off) {
   return *(const ZP_LDS bf16x8 *)((const ZP_LDS char *)smem + off);
-}
-__device__ __forceinline__ void zp_lds_write16(char *smem, int off, u32x4 v) {
-  *(ZP_LDS u32x4 *)((ZP_LDS char *)smem + off) = v;
 }
 // Within each group of 16 lanes, lane i passes the address of 4 consecutive 16-bit elements of row i/4,
 // columns 4*(i%4)..+3 of a 4x16 block, and receives column i of rows 0..3.
@@ -86,24 +83,6 @@ __device__ __forceinline__ bf16x4 zp_lds_read_tr(const char *smem, int off) {
 
 __device__ __forceinline__ bf16x8 zp_cat(bf16x4 a, bf16x4 b) {
   return __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
-}
-
-// Byte offset of 16-byte chunk c of row `row` in a [rows][D] bf16 LDS tile read row-wise as an MFMA
-// operand (16 consecutive lanes read the same chunk of 16 consecutive rows): the chunk index is XORed
-// with the row so those 16 reads spread over all banks.
-template <int D>
-__device__ __forceinline__ int zp_koff(int row, int c) {
-  if (D == 128) return row * 256 + ((c ^ (row & 15)) << 4);
-  return row * 128 + ((c ^ ((row >> 1) & 7)) << 4);
-}
-// Byte offset of element column `col` (multiple of 4) of row `row` in a [rows][D] bf16 LDS tile read with
-// the transposing read (a wave reads 8 consecutive rows x 64 contiguous bytes): 64-byte segments are XORed
-// with the row so 4 consecutive rows land in 4 different bank quarters.
-template <int D>
-__device__ __forceinline__ int zp_voff(int row, int col) {
-  int b = col * 2, seg = b >> 6, within = b & 63;
-  if (D == 128) return row * 256 + (((seg ^ (row & 3))) << 6) + within;
-  return row * 128 + ((seg ^ ((row >> 1) & 1)) << 6) + within;
 }
 
 // Swizzle for LDS tiles that are read BOTH row-wise (16 lanes: 16 consecutive rows, same 16-byte chunk) and
@@ -136,32 +115,6 @@ __device__ __forceinline__ void zp_dma4(const void *g, unsigned lds_base_uniform
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off\n" ::"v"(g), "s"(lds_base_uniform) : "memory");
 }
 
-// Staging of a [64][D] bf16 tile in the zp_swz layout without passing through registers: the swizzle is
-// applied by choosing WHICH global chunk a lane fetches. Rows past rows_total are clamped to the last valid
-// row (the callers mask them). 256 threads; every wave issues 64*D*2/4096 loads.
-template <int D>
-__device__ __forceinline__ void zp_stage_async(char *lds_tile, const __bf16 *gbase, int64_t stride, int row0,
-                                               int rows_total, int tid) {
-  const int lane = tid & 63;
-  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  constexpr int PER_WAVE = 64 * D * 2 / 1024 / 4;  // 1 KiB wave-loads per wave
-  const unsigned lds0 = __builtin_amdgcn_readfirstlane(zp_lds_addr(lds_tile));
-#pragma unroll
-  for (int n = 0; n < PER_WAVE; n++) {
-    const int blk = w * PER_WAVE + n;  // 1 KiB block of the tile
-    int r, c;
-    if (D == 128) {
-      r = blk * 4 + (lane >> 4);
-      c = (lane & 15) ^ (((r & 3) << 2) | ((r >> 2) & 3));
-    } else {
-      r = blk * 8 + (lane >> 3);
-      c = (lane & 7) ^ (((r & 1) << 2) | ((r >> 1) & 3));
-    }
-    int gr = row0 + r;
-    if (gr > rows_total - 1) gr = rows_total - 1;
-    zp_dma16(gbase + (int64_t)gr * stride + c * 8, lds0 + blk * 1024);
-  }
-}
 // Copy of 64 consecutive floats (one per lane), issued by every wave of the workgroup to the same
 // destination so that all waves have the same number of loads in flight.
 __device__ __forceinline__ void zp_stage_async_f32x64(float *lds_dst, const float *gsrc, int first, int last_valid,
