@@ -53,6 +53,9 @@ WORKLOADS = {
     # (forward merged in place, backward accumulated in fp32)
     "node-p8-longtail-128k": dict(T=131072, Hq=32, Hkv=8, d=128, seed=1003, mix="longtail", C=0, bwd=True, remap=True,
                                   node=dict(P=8, N=1, L=20480)),
+    # the 256K lognormal slice with the partitioner's placement in place of the stand-in layout (capacity 36864)
+    "node-p8-lognormal-256k-gqa64x8": dict(T=262144, Hq=64, Hkv=8, d=128, seed=1005, mix="lognormal", C=0, bwd=True,
+                                           remap=True, node=dict(P=8, N=1, L=36864)),
 }
 
 
@@ -169,7 +172,7 @@ class NodeBenchJob:
         w = WORKLOADS[name]
         self.name, self.w, self.dev = name, w, dev
         T, Hq, Hkv, d = w["T"], w["Hq"], w["Hkv"], w["d"]
-        lengths, _ = synth.lengths_longtail(T, w["seed"])
+        lengths = synth.lengths_longtail(T, w["seed"])[0] if w["mix"] == "longtail" else synth.lengths_lognormal(T, w["seed"])
         nd = w["node"]
         self.plan = NodePlan(lengths, nd["P"], nd["N"], nd["L"], b_intra=1, b_inter=8)
         self.job = NodeJob(self.plan, Hq, Hkv, d, dev)
