@@ -45,14 +45,18 @@ __device__ __forceinline__ void fwd_tile(const char *Kb, const char *Vb, const b
       if (j + 32 >= nvis_lane) s1[r] = -INFINITY;
     }
   }
-  // two chains of three-operand maxima over the lane's 32 scores
-  float ta = zp_max3(s0[0], s0[1], s1[0]);
-  float tb = zp_max3(s1[1], s1[2], s1[3]);
+  // Two chains of three-operand maxima over the lane's 32 scores. The compiler does not check the inline-assembly
+  // v_max3 against the "MFMA result read too early" hazard, so both chains start from t0, an ordinary fmaxf of one
+  // register of each accumulator: the wait states the compiler inserts before t0 cover every later read.
+  const float t0 = fmaxf(s0[15], s1[15]);
+  float ta = zp_max3(t0, s0[0], s0[1]);
+  float tb = zp_max3(t0, s1[0], s1[1]);
 #pragma unroll
-  for (int r = 2; r < 16; r += 2) ta = zp_max3(ta, s0[r], s0[r + 1]);
-#pragma unroll
-  for (int r = 4; r < 16; r += 2) tb = zp_max3(tb, s1[r], s1[r + 1]);
-  const float tmax = zp_pair_max(zp_max3(ta, tb, tb));
+  for (int r = 2; r < 14; r += 2) {
+    ta = zp_max3(ta, s0[r], s0[r + 1]);
+    tb = zp_max3(tb, s1[r], s1[r + 1]);
+  }
+  const float tmax = zp_pair_max(zp_max3(ta, tb, fmaxf(s0[14], s1[14])));
   const float tmc = tmax * c_log2;
   // the reference maximum moves only when the tile maximum exceeds it by more than 2^8
   if (__builtin_amdgcn_ballot_w64(tmc > mc + 8.0f) != 0) {

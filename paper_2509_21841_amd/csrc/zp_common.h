@@ -54,7 +54,10 @@ __device__ __forceinline__ void zp_block_to_unit(int bid, int grp, int &unit, in
 
 __device__ __forceinline__ float zp_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// Three-operand maximum in one VALU operation (operands are finite or -inf here, never NaN).
+// Three-operand maximum in one VALU operation (operands are finite or -inf here, never NaN). Inline assembly is
+// invisible to the compiler's hazard checks: never feed it a register an MFMA has just written unless an ordinary
+// instruction that reads the same accumulator comes first (data-dependently), which makes the compiler insert the
+// required wait states.
 __device__ __forceinline__ float zp_max3(float a, float b, float c) {
   float d;
   asm("v_max3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
@@ -104,15 +107,18 @@ __device__ __forceinline__ int zp_swz_col(int row, int col) {
 // The direct-to-LDS loads are issued from inline assembly so that they stay truly asynchronous: the
 // compiler does not track them, inserts no waits for them, and its workgroup barriers do not drain them.
 // Ordering is explicit: zp_wait_async*() before the barrier that publishes a staged tile. Each lane's bytes
-// land at (wave-uniform LDS base in M0) + lane * size.
+// land at (wave-uniform LDS base in M0) + lane * size. The compiler checks no hardware hazard for inline assembly,
+// so each block pads itself: s_mov m0 plus s_nop 3 put five wait states between any vector instruction that
+// wrote the scalar base (a v_readlane restoring a spilled SGPR, a v_readfirstlane) and the load that reads it,
+// and cover the one wait state M0 needs before a direct-to-LDS load.
 __device__ __forceinline__ unsigned zp_lds_addr(const void *p) {
   return (unsigned)(unsigned long long)(ZP_LDS const char *)p;
 }
 __device__ __forceinline__ void zp_dma16(const void *g, unsigned lds_base_uniform) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off\n" ::"v"(g), "s"(lds_base_uniform) : "memory");
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 3\n\tglobal_load_lds_dwordx4 %0, off\n" ::"v"(g), "s"(lds_base_uniform) : "memory");
 }
 __device__ __forceinline__ void zp_dma4(const void *g, unsigned lds_base_uniform) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off\n" ::"v"(g), "s"(lds_base_uniform) : "memory");
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 3\n\tglobal_load_lds_dword %0, off\n" ::"v"(g), "s"(lds_base_uniform) : "memory");
 }
 
 // Copy of 64 consecutive floats (one per lane), issued by every wave of the workgroup to the same
@@ -133,7 +139,7 @@ __device__ __forceinline__ void zp_wait_async_upto() {
 
 // 16-byte direct-to-LDS load addressed as (wave-uniform 64-bit base) + (per-lane 32-bit byte offset)
 __device__ __forceinline__ void zp_dma16_so(const void *sbase_uniform, unsigned voff, unsigned lds_base_uniform) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1\n" ::"v"(voff), "s"(sbase_uniform),
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 3\n\tglobal_load_lds_dwordx4 %0, %1\n" ::"v"(voff), "s"(sbase_uniform),
                "s"(lds_base_uniform)
                : "memory");
 }
