@@ -155,6 +155,34 @@ def test_fwd_deterministic():
     assert torch.equal(a[0].view(torch.int16), b[0].view(torch.int16)) and torch.equal(a[1], b[1])
 
 
+@pytest.mark.parametrize("lengths,Hq,Hkv,d", [([513, 200], 4, 2, 128), ([129, 64, 300, 1], 2, 2, 64), ([2049], 8, 2, 128)])
+def test_every_entry_point_is_deterministic(lengths, Hq, Hkv, d):
+    """Three runs of forward, backward, the chunked paths and the merge give bit-identical results."""
+    (q, k, v, do), cu = make(lengths, Hq, Hkv, d, 59, with_dout=True)
+    T = q.shape[0]
+    L = lengths[0]
+    pairs, merges, rows = B.chunk_pairs(0, L, 4)
+    runs = []
+    for _ in range(3):
+        o, lse = B.varlen_attn_fwd(q, k, v, cu)
+        dq, dk, dv = B.varlen_attn_bwd(do, q, k, v, o, lse, cu)
+        op, lp = B.chunk_attn_partial(q, k, v, pairs, rows)
+        o2 = torch.zeros_like(o); lse2 = torch.zeros_like(lse)
+        B.lse_merge(op, lp, merges, o2, lse2)
+        o_run = torch.zeros((T, Hq, d), dtype=torch.float32, device=DEV)
+        lse_run = torch.full((Hq, T), float("-inf"), dtype=torch.float32, device=DEV)
+        acc = [torch.zeros(x.shape, dtype=torch.float32, device=DEV) for x in (q, k, v)]
+        for rnd in B.ring_rounds(pairs, 4):
+            B.chunk_attn_update(q, k, v, rnd, o_run, lse_run)
+            B.chunk_attn_partial_bwd(do, q, k, v, o, lse, rnd, *acc)
+        torch.cuda.synchronize()
+        runs.append([t.clone() for t in (o, lse, dq, dk, dv, op[:rows], lp[:, :rows], o2, lse2, o_run[:L], lse_run[:, :L], *acc)])
+    bits = lambda t: t.view(torch.int16) if t.dtype == torch.bfloat16 else t.view(torch.int32)
+    for other in runs[1:]:
+        for a, b in zip(runs[0], other):
+            assert torch.equal(bits(a), bits(b))
+
+
 # ---- partials ----------------------------------------------------------------------------------------
 @pytest.mark.parametrize("L,C,Hq,Hkv,d", [(1000, 4, 4, 1, 128), (257, 3, 2, 2, 64), (130, 4, 2, 1, 128)])
 def test_chunked_then_merged_equals_whole(L, C, Hq, Hkv, d):
