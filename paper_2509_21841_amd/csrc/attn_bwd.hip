@@ -135,8 +135,16 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
   const int nvis_w_min = nvis_of(w * 32), nvis_w_max = nvis_of(w * 32 + 31);
   const int n_kt = (nvis_of(t.q_rows - 1) + 63) / 64;
 
-  bf16x8 qreg[D / 16], doreg[D / 16];
-  float dsum = 0.f;
+  zp_stager<D> kst, vst;
+  kst.init(p.k + (int64_t)t.k_tok0 * p.k_stride + (int64_t)g * D, p.k_stride, tid);
+  vst.init(p.v + (int64_t)t.k_tok0 * p.v_stride + (int64_t)g * D, p.v_stride, tid);
+  zp_lds_offsets<D> lo;
+  lo.init(lane);
+
+  // Row operands first, the first tile copy right behind them (the two memory latencies overlap), their first use
+  // after that. The explicit wait before the first barrier covers all of it and tells the compiler that the register
+  // operands have arrived (a wait of its own inside the key loop would drain the copies in flight every iteration).
+  bf16x8 qreg[D / 16], doreg[D / 16], oreg[D / 16];
   {
     const __bf16 *qp = p.q + tok * p.q_stride + (int64_t)h * D + 8 * hi;
     const __bf16 *dop = p.dout + tok * p.do_stride + (int64_t)h * D + 8 * hi;
@@ -146,19 +154,28 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
       if (row_ok) {
         qreg[kk] = *(const bf16x8 *)(qp + 16 * kk);
         doreg[kk] = *(const bf16x8 *)(dop + 16 * kk);
-        bf16x8 ov = *(const bf16x8 *)(op + 16 * kk);
-#pragma unroll
-        for (int e = 0; e < 8; e++) dsum += (float)doreg[kk][e] * (float)ov[e];
+        oreg[kk] = *(const bf16x8 *)(op + 16 * kk);
       } else {
         qreg[kk] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
         doreg[kk] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+        oreg[kk] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
       }
     }
   }
+  float lse_nat = 0.f;
+  if (row_ok) lse_nat = p.lse[(int64_t)h * p.T + tok];
+  if (n_kt > 0) {
+    kst.issue(Ks, 0, t.k_len);
+    vst.issue(Vs, 0, t.k_len);
+  }
+  float dsum = 0.f;
+#pragma unroll
+  for (int kk = 0; kk < D / 16; kk++)
+#pragma unroll
+    for (int e = 0; e < 8; e++) dsum += (float)doreg[kk][e] * (float)oreg[kk][e];
   const float Dq = zp_pair_sum(dsum);
   float lse2 = 0.f;
   if (row_ok) {
-    const float lse_nat = p.lse[(int64_t)h * p.T + tok];
     lse2 = lse_nat * LOG2E;
     if (hi == 0) {
       // negated and pre-divided so that the second kernel can seed its MFMA accumulators with them
@@ -166,14 +183,6 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
       p.lse2[(int64_t)h * p.T + tok] = -lse_nat / p.scale;
     }
   }
-  // every register operand has arrived before the first asynchronous tile copy is issued
-  zp_wait_async();
-
-  zp_stager<D> kst, vst;
-  kst.init(p.k + (int64_t)t.k_tok0 * p.k_stride + (int64_t)g * D, p.k_stride, tid);
-  vst.init(p.v + (int64_t)t.k_tok0 * p.v_stride + (int64_t)g * D, p.v_stride, tid);
-  zp_lds_offsets<D> lo;
-  lo.init(lane);
 
   f32x16 dq_acc[D / 32];
 #pragma unroll
@@ -182,10 +191,6 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
     for (int r = 0; r < 16; r++) dq_acc[i][r] = 0.f;
   const float c_log2 = p.scale_log2;
 
-  if (n_kt > 0) {
-    kst.issue(Ks, 0, t.k_len);
-    vst.issue(Vs, 0, t.k_len);
-  }
   zp_wait_async();
   __syncthreads();
 
@@ -406,10 +411,6 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
     }
   }
 
-  // the register operands must have arrived before any asynchronous tile copy is issued: a later wait for
-  // them would also drain those copies
-  zp_wait_async();
-
   f32x16 dk_acc[D / 32], dv_acc[D / 32];
 #pragma unroll
   for (int i = 0; i < D / 32; i++)
@@ -440,13 +441,13 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
     zp_stage_async_f32x64(Ds + buf * 64, p.dvec + base, i0, t.q_rows - 1, lane);
   };
 
-  // prologue: up to NBUF-1 tiles in flight; tile 0 must have landed before the first iteration
+  // prologue: tile 0 is requested right behind the K/V register operands (the two memory latencies overlap) and
+  // one explicit wait covers both -- it also tells the compiler that the register operands have arrived (a wait of
+  // its own inside the loop would drain the copies in flight every iteration); tiles 1 and 2 follow and stay in flight
   if (n_it > 0) stage(0);
+  zp_wait_async();
   if (n_it > 1) stage(1);
   if (n_it > 2) stage(2);
-  if (n_it > 2) zp_wait_async_upto<2 * LOADS>();
-  else if (n_it > 1) zp_wait_async_upto<LOADS>();
-  else zp_wait_async();
   __syncthreads();
 
   const int kpos_w_min = t.k_pos0 + w * 32, kpos_w_max = t.k_pos0 + w * 32 + 31;
