@@ -61,6 +61,16 @@ __device__ __forceinline__ void add_acc_rows(float *dst, const f32x16 (&acc)[D /
     }
 }
 
+template <class F, int... I>
+__device__ __forceinline__ void zp_static_for_impl(F &&f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in order
+template <int N, class F>
+__device__ __forceinline__ void zp_static_for(F &&f) {
+  zp_static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
 // ------------------------------------------------------------------------------------------- dQ
 // One 32-key half of a K/V tile for one wave: S^T and dP^T chains, dS^T, then dQ^T += K^T dS^T.
 template <int D, bool MASK>
@@ -258,11 +268,15 @@ __device__ __forceinline__ void dkdv_pds(const f32x16 &s, const f32x16 &dp, int 
 // One 64-query tile = two 32-query blocks, processed in phases with the LDS operands of the next phase
 // requested before the arithmetic of the current one:
 //   rows(0) | S,dP(0) | tr(0) requested, P,dS(0) | rows(1) requested, dV,dK(0) | S,dP(1) | tr(1), P,dS(1) | dV,dK(1)
-template <int D, bool MASK>
+// `piece(integral_constant<int, n>)` is called after the n-th MFMA of the last phase (n = 0 .. 4 * D / 32 - 1):
+// the caller's asynchronous copies of a later tile are issued there, one load between two MFMAs, where nothing
+// else competes for the issue slot.
+template <int D, bool MASK, class Piece>
 __device__ __forceinline__ void dkdv_tile(const char *Qb, const char *Ob, const float *Lb, const float *Db,
                                           const bf16x8 (&kreg)[D / 16], const bf16x8 (&vreg)[D / 16],
                                           f32x16 (&dk_acc)[D / 32], f32x16 (&dv_acc)[D / 32], int qpos0, int kpos,
-                                          int qpos_end, float c_log2, int hi, const zp_lds_offsets<D> &lo) {
+                                          int qpos_end, float c_log2, int hi, const zp_lds_offsets<D> &lo,
+                                          Piece &&piece) {
   constexpr int KK = D / 16, DB = D / 32;
   bf16x8 aq[KK], ao[KK];
   bf16x8 to[2][DB], tq[2][DB];
@@ -358,18 +372,21 @@ __device__ __forceinline__ void dkdv_tile(const char *Qb, const char *Ob, const 
   for (int i = 0; i < 4 * DB; i++) { ZP_SGB(ZP_SG_MFMA, 1); ZP_SGB(ZP_SG_TRANS, 1); ZP_SGB(ZP_SG_VALU, 3); ZP_SGB(ZP_SG_DSREAD, 2); }
   __builtin_amdgcn_sched_barrier(0);
 
-  // D: dV,dK(1)
-#pragma unroll
-  for (int m = 0; m < 2; m++)
-#pragma unroll
-    for (int db = 0; db < DB; db++)
-      dv_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(to1[m][db], pb[1][m], dv_acc[db], 0, 0, 0);
-#pragma unroll
-  for (int m = 0; m < 2; m++)
-#pragma unroll
-    for (int db = 0; db < DB; db++)
-      dk_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq1[m][db], dsb[1][m], dk_acc[db], 0, 0, 0);
-  __builtin_amdgcn_sched_barrier(0);
+  // D: dV,dK(1), the caller's copies in between
+  zp_static_for<2 * DB>([&](auto n) {
+    constexpr int m = n.value / DB, db = n.value % DB;
+    dv_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(to1[m][db], pb[1][m], dv_acc[db], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    piece(n);
+    __builtin_amdgcn_sched_barrier(0);
+  });
+  zp_static_for<2 * DB>([&](auto n) {
+    constexpr int m = n.value / DB, db = n.value % DB;
+    dk_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq1[m][db], dsb[1][m], dk_acc[db], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    piece(std::integral_constant<int, 2 * DB + n.value>{});
+    __builtin_amdgcn_sched_barrier(0);
+  });
 }
 
 template <int D>
@@ -440,6 +457,33 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
     zp_stage_async_f32x64(Ls + buf * 64, p.lse2 + base, i0, t.q_rows - 1, lane);
     zp_stage_async_f32x64(Ds + buf * 64, p.dvec + base, i0, t.q_rows - 1, lane);
   };
+  // The same copies for a tile of 64 valid rows, cut into pieces that dkdv_tile issues between the MFMAs of its
+  // last phase: piece 0 is the scalar address arithmetic, every later piece one load (same order as `stage`).
+  constexpr int PW = zp_stager<D>::PER_WAVE;
+  const void *pc_q = nullptr, *pc_o = nullptr, *pc_l = nullptr, *pc_d = nullptr;
+  unsigned pc_buf = 0;
+  auto stage_piece = [&](auto n) {
+    constexpr int N = decltype(n)::value;
+    if constexpr (N == 0) {
+      const int hh = st_hh, i0 = st_qt * 64;
+      const int h = g * p.grp + hh;
+      if (++st_hh == p.grp) { st_hh = 0; st_qt--; }
+      pc_q = zp_uniform_ptr(qst.base + (int64_t)i0 * qst.stride + (int64_t)hh * D);
+      pc_o = zp_uniform_ptr(ost.base + (int64_t)i0 * ost.stride + (int64_t)hh * D);
+      const int64_t base = (int64_t)h * p.T + t.q_tok0 + i0;
+      pc_l = zp_uniform_ptr(p.lse2 + base);
+      pc_d = zp_uniform_ptr(p.dvec + base);
+    } else if constexpr (N <= PW) {
+      zp_dma16_so(pc_q, qst.off[N - 1], __builtin_amdgcn_readfirstlane(zp_lds_addr(Qs) + pc_buf * TILEB + (qst.w * PW + N - 1) * 1024));
+    } else if constexpr (N <= 2 * PW) {
+      zp_dma16_so(pc_o, ost.off[N - PW - 1], __builtin_amdgcn_readfirstlane(zp_lds_addr(Os) + pc_buf * TILEB + (ost.w * PW + N - PW - 1) * 1024));
+    } else if constexpr (N == 2 * PW + 1) {
+      zp_dma4_so(pc_l, lane * 4, __builtin_amdgcn_readfirstlane(zp_lds_addr(Ls) + pc_buf * 256));
+    } else if constexpr (N == 2 * PW + 2) {
+      zp_dma4_so(pc_d, lane * 4, __builtin_amdgcn_readfirstlane(zp_lds_addr(Ds) + pc_buf * 256));
+    }
+  };
+  auto no_piece = [](auto) {};
 
   // prologue: tile 0 is requested right behind the K/V register operands (the two memory latencies overlap) and
   // one explicit wait covers both -- it also tells the compiler that the register operands have arrived (a wait of
@@ -458,16 +502,25 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
     const int i0 = cur_qt * 64;
     if (++cur_hh == p.grp) { cur_hh = 0; cur_qt--; }
     const int ahead = n_it - 1 - it;  // tiles after this one
-    if (ahead >= NBUF - 1) stage((buf + NBUF - 1) & (NBUF - 1));
-
     const int qpos0 = t.q_pos0 + i0;  // position of the tile's first query
-    if (qpos0 + 63 >= kpos_w_min) {   // otherwise every query of the tile precedes every key of this wave
+    const bool compute = qpos0 + 63 >= kpos_w_min;  // otherwise every query of the tile precedes every key of this wave
+    const bool masked = qpos0 < kpos_w_max || qpos0 + 64 > qpos_end;
+    // the tile three iterations ahead is fetched inside this tile's arithmetic when it is a full tile and this
+    // wave computes an unmasked one (the common case), else in front of it
+    const bool fetch = ahead >= NBUF - 1;
+    const bool fused = fetch && compute && !masked && st_qt * 64 + 64 <= t.q_rows;
+    pc_buf = (buf + NBUF - 1) & (NBUF - 1);
+    if (fetch && !fused) stage(pc_buf);
+
+    if (compute) {
       const char *Qb = Qs + buf * TILEB;
       const char *Ob = Os + buf * TILEB;
-      if (qpos0 < kpos_w_max || qpos0 + 64 > qpos_end)
-        dkdv_tile<D, true>(Qb, Ob, Ls + buf * 64, Ds + buf * 64, kreg, vreg, dk_acc, dv_acc, qpos0, kpos, qpos_end, c_log2, hi, lo);
+      if (masked)
+        dkdv_tile<D, true>(Qb, Ob, Ls + buf * 64, Ds + buf * 64, kreg, vreg, dk_acc, dv_acc, qpos0, kpos, qpos_end, c_log2, hi, lo, no_piece);
+      else if (fused)
+        dkdv_tile<D, false>(Qb, Ob, Ls + buf * 64, Ds + buf * 64, kreg, vreg, dk_acc, dv_acc, qpos0, kpos, qpos_end, c_log2, hi, lo, stage_piece);
       else
-        dkdv_tile<D, false>(Qb, Ob, Ls + buf * 64, Ds + buf * 64, kreg, vreg, dk_acc, dv_acc, qpos0, kpos, qpos_end, c_log2, hi, lo);
+        dkdv_tile<D, false>(Qb, Ob, Ls + buf * 64, Ds + buf * 64, kreg, vreg, dk_acc, dv_acc, qpos0, kpos, qpos_end, c_log2, hi, lo, no_piece);
     }
     // the next tile must have landed; the ones behind it may stay in flight
     if (ahead >= NBUF - 1) zp_wait_async_upto<(NBUF - 2) * LOADS>();

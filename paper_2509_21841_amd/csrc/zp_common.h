@@ -143,6 +143,12 @@ __device__ __forceinline__ void zp_dma16_so(const void *sbase_uniform, unsigned 
                "s"(lds_base_uniform)
                : "memory");
 }
+// the same with 4 bytes per lane
+__device__ __forceinline__ void zp_dma4_so(const void *sbase_uniform, unsigned voff, unsigned lds_base_uniform) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 3\n\tglobal_load_lds_dword %0, %1\n" ::"v"(voff), "s"(sbase_uniform),
+               "s"(lds_base_uniform)
+               : "memory");
+}
 __device__ __forceinline__ const void *zp_uniform_ptr(const void *p) {
   unsigned long long v = (unsigned long long)p;
   unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v), hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
