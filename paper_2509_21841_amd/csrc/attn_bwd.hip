@@ -61,42 +61,36 @@ __device__ __forceinline__ void add_acc_rows(float *dst, const f32x16 (&acc)[D /
     }
 }
 
-template <class F, int... I>
-__device__ __forceinline__ void zp_static_for_impl(F &&f, std::integer_sequence<int, I...>) {
-  (f(std::integral_constant<int, I>{}), ...);
-}
-// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in order
-template <int N, class F>
-__device__ __forceinline__ void zp_static_for(F &&f) {
-  zp_static_for_impl(f, std::make_integer_sequence<int, N>{});
-}
-
 // ------------------------------------------------------------------------------------------- dQ
 // One 32-key half of a K/V tile for one wave: S^T and dP^T chains, dS^T, then dQ^T += K^T dS^T.
-template <int D, bool MASK>
+// `piece(integral_constant<int, kk>)` is called once per 16-wide k-step of the chains when PIECES is set, in program
+// order between the LDS operand reads of step kk and those of step kk + 1: the caller issues one asynchronous copy
+// of the next tile there. The copies are ordered against every LDS access, the reads are pinned to the MFMAs by the
+// scheduling groups below, so the copies end up one per MFMA pair -- far enough apart that none waits for the
+// address unit behind the copies of the other three waves.
+template <int D, bool MASK, bool PIECES, class Piece>
 __device__ __forceinline__ void dq_half(const char *Kb, const char *Vb, int kb, const bf16x8 (&qreg)[D / 16],
                                         const bf16x8 (&doreg)[D / 16], f32x16 (&dq_acc)[D / 32], float c_log2,
                                         float lse2, const f32x16 &negD, int j0, int hi, int nvis_lane,
-                                        const zp_lds_offsets<D> &lo) {
+                                        const zp_lds_offsets<D> &lo, Piece &&piece) {
   constexpr int KK = D / 16, DB = D / 32;
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   // the dP^T chain starts from -D (a lane holds one query, so the seed is the same in all 16 registers and lives in
   // registers for the whole kernel): the accumulator then holds dP - D
-  f32x16 s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo.rows(Kb, kb, 0), qreg[0], zero, 0, 0, 0);
-  f32x16 dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo.rows(Vb, kb, 0), doreg[0], negD, 0, 0, 0);
-#pragma unroll
-  for (int kk = 1; kk < KK; kk++) {
-    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo.rows(Kb, kb, kk), qreg[kk], s, 0, 0, 0);
-    dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo.rows(Vb, kb, kk), doreg[kk], dp, 0, 0, 0);
-  }
-  // keep the LDS operand reads only a step ahead of the MFMAs that use them (register budget of two waves per SIMD)
-  ZP_SGB(ZP_SG_DSREAD, 4);
-#pragma unroll
-  for (int kk = 0; kk < KK - 2; kk++) {
-    ZP_SGB(ZP_SG_MFMA, 2);
-    ZP_SGB(ZP_SG_DSREAD, 2);
-  }
-  ZP_SGB(ZP_SG_MFMA, 4);
+  // the LDS operand reads stay two k-steps ahead of the MFMAs that use them; every step is fenced so that the
+  // copies keep their distance
+  f32x16 s = zero, dp = negD;
+  bf16x8 ka[KK], va[KK];
+  ka[0] = lo.rows(Kb, kb, 0); va[0] = lo.rows(Vb, kb, 0);
+  ka[1] = lo.rows(Kb, kb, 1); va[1] = lo.rows(Vb, kb, 1);
+  zp_static_for<KK>([&](auto kk) {
+    constexpr int k = kk.value;
+    __builtin_amdgcn_sched_barrier(0);
+    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[k], qreg[k], s, 0, 0, 0);
+    dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[k], doreg[k], dp, 0, 0, 0);
+    if constexpr (k + 2 < KK) { ka[k + 2] = lo.rows(Kb, kb, k + 2); va[k + 2] = lo.rows(Vb, kb, k + 2); }
+    if constexpr (PIECES) piece(kk);
+  });
   __builtin_amdgcn_sched_barrier(0);
   bf16x8 dsb[2];
 #pragma unroll
@@ -207,23 +201,45 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
   f32x16 negD;
 #pragma unroll
   for (int r = 0; r < 16; r++) negD[r] = -Dq;
+  constexpr int PW = zp_stager<D>::PER_WAVE;
   // one key tile out of LDS buffer BUF (compile-time, so that every LDS address is a register plus an immediate)
   auto key_tile = [&](int it, auto BUF) {
     constexpr int buf = decltype(BUF)::value;
     const int j0 = it * 64;
-    if (it + 1 < n_kt) {
+    const bool compute = j0 < nvis_w_max;
+    const bool masked = j0 + 64 > nvis_w_min;
+    // the next tile is fetched inside the first half of this tile's arithmetic when it has 64 valid keys and this
+    // wave computes an unmasked tile (the common case), else in front of it
+    const bool fetch = it + 1 < n_kt;
+    const bool fused = fetch && compute && !masked && j0 + 128 <= t.k_len;
+    if (fetch && !fused) {
       kst.issue(Ks + (buf ^ 1) * TILEB, j0 + 64, t.k_len);
       vst.issue(Vs + (buf ^ 1) * TILEB, j0 + 64, t.k_len);
     }
-    if (j0 < nvis_w_max) {
+    // the same copies one load at a time, K and V alternating (2 * PW loads = one per k-step)
+    // (the sources are worked out unconditionally: a value defined under a branch would not stay in scalar registers)
+    const void *pc_k = zp_uniform_ptr(kst.base + (int64_t)(j0 + 64) * kst.stride);
+    const void *pc_v = zp_uniform_ptr(vst.base + (int64_t)(j0 + 64) * vst.stride);
+    auto stage_piece = [&](auto n) {
+      constexpr int N = decltype(n)::value, i = N / 2;
+      static_assert(2 * PW == D / 16, "one copy per k-step");
+      if constexpr (N % 2 == 0)
+        zp_dma16_so(pc_k, kst.off[i], __builtin_amdgcn_readfirstlane(zp_lds_addr(Ks + (buf ^ 1) * TILEB) + (kst.w * PW + i) * 1024));
+      else
+        zp_dma16_so(pc_v, vst.off[i], __builtin_amdgcn_readfirstlane(zp_lds_addr(Vs + (buf ^ 1) * TILEB) + (vst.w * PW + i) * 1024));
+    };
+    if (compute) {
       const char *Kb = Ks + buf * TILEB;
       const char *Vb = Vs + buf * TILEB;
-      if (j0 + 64 > nvis_w_min) {
-        dq_half<D, true>(Kb, Vb, 0, qreg, doreg, dq_acc, c_log2, lse2, negD, j0, hi, nvis_lane, lo);
-        dq_half<D, true>(Kb, Vb, 1, qreg, doreg, dq_acc, c_log2, lse2, negD, j0, hi, nvis_lane, lo);
+      if (masked) {
+        dq_half<D, true, false>(Kb, Vb, 0, qreg, doreg, dq_acc, c_log2, lse2, negD, j0, hi, nvis_lane, lo, stage_piece);
+        dq_half<D, true, false>(Kb, Vb, 1, qreg, doreg, dq_acc, c_log2, lse2, negD, j0, hi, nvis_lane, lo, stage_piece);
+      } else if (fused) {
+        dq_half<D, false, true>(Kb, Vb, 0, qreg, doreg, dq_acc, c_log2, lse2, negD, j0, hi, nvis_lane, lo, stage_piece);
+        dq_half<D, false, false>(Kb, Vb, 1, qreg, doreg, dq_acc, c_log2, lse2, negD, j0, hi, nvis_lane, lo, stage_piece);
       } else {
-        dq_half<D, false>(Kb, Vb, 0, qreg, doreg, dq_acc, c_log2, lse2, negD, j0, hi, nvis_lane, lo);
-        dq_half<D, false>(Kb, Vb, 1, qreg, doreg, dq_acc, c_log2, lse2, negD, j0, hi, nvis_lane, lo);
+        dq_half<D, false, false>(Kb, Vb, 0, qreg, doreg, dq_acc, c_log2, lse2, negD, j0, hi, nvis_lane, lo, stage_piece);
+        dq_half<D, false, false>(Kb, Vb, 1, qreg, doreg, dq_acc, c_log2, lse2, negD, j0, hi, nvis_lane, lo, stage_piece);
       }
     }
     zp_wait_async();

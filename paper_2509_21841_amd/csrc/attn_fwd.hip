@@ -25,17 +25,37 @@ struct FwdCfg {
 };
 
 // One 64-key tile for one wave of 32 query rows.
-template <int D, bool MASK>
+// With PIECES, `piece(integral_constant<int, kk>)` is called once per 16-wide k-step of the score MFMAs: the caller
+// issues one asynchronous copy of the next tile there. The steps are fenced, so the copies stay one MFMA pair apart
+// -- far enough that none waits for the address unit behind the copies of the other waves, which is what issuing
+// them back to back in front of the tile costs.
+template <int D, bool MASK, bool PIECES, class Piece>
 __device__ __forceinline__ void fwd_tile(const char *Kb, const char *Vb, const bf16x8 (&qreg)[D / 16],
                                          f32x16 (&o_acc)[D / 32], float &mc, float &l_sum, float c_log2, int j0,
-                                         int hi, int nvis_lane, const zp_lds_offsets<D> &lo) {
+                                         int hi, int nvis_lane, const zp_lds_offsets<D> &lo, Piece &&piece) {
   constexpr int KK = D / 16, DB = D / 32;
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   f32x16 s0 = zero, s1 = zero;
+  if constexpr (PIECES) {
+    // the K row operands stay two k-steps ahead of the MFMAs that use them
+    bf16x8 k0[KK], k1[KK];
+    k0[0] = lo.rows(Kb, 0, 0); k1[0] = lo.rows(Kb, 1, 0);
+    k0[1] = lo.rows(Kb, 0, 1); k1[1] = lo.rows(Kb, 1, 1);
+    zp_static_for<KK>([&](auto kk) {
+      constexpr int k = kk.value;
+      __builtin_amdgcn_sched_barrier(0);
+      s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0[k], qreg[k], s0, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1[k], qreg[k], s1, 0, 0, 0);
+      if constexpr (k + 2 < KK) { k0[k + 2] = lo.rows(Kb, 0, k + 2); k1[k + 2] = lo.rows(Kb, 1, k + 2); }
+      piece(kk);
+    });
+    __builtin_amdgcn_sched_barrier(0);
+  } else {
 #pragma unroll
-  for (int kk = 0; kk < KK; kk++) {
-    s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo.rows(Kb, 0, kk), qreg[kk], s0, 0, 0, 0);
-    s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo.rows(Kb, 1, kk), qreg[kk], s1, 0, 0, 0);
+    for (int kk = 0; kk < KK; kk++) {
+      s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo.rows(Kb, 0, kk), qreg[kk], s0, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo.rows(Kb, 1, kk), qreg[kk], s1, 0, 0, 0);
+    }
   }
   if (MASK) {
 #pragma unroll
@@ -156,19 +176,39 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   zp_wait_async();
   __syncthreads();
 
+  constexpr int PW = zp_stager<D>::PER_WAVE;
   // one key tile out of LDS buffer BUF (a compile-time constant, so every LDS address is register + immediate)
   auto key_tile = [&](int it, auto BUF) {
     constexpr int buf = decltype(BUF)::value;
     const int j0 = it * BN;
-    if (it + 1 < n_kt) {
+    const bool compute = j0 < nvis_w_max;  // otherwise every key of this tile is masked for the whole wave
+    const bool masked = j0 + BN > nvis_w_min;
+    // the next tile is fetched inside this tile's score MFMAs when it has 64 valid keys and this wave computes an
+    // unmasked tile (the common case), else in front of it
+    const bool fetch = it + 1 < n_kt;
+    const bool fused = fetch && compute && !masked && j0 + 2 * BN <= t.k_len;
+    if (fetch && !fused) {
       kst.issue(Ks + (buf ^ 1) * C::TILEB, j0 + BN, t.k_len);
       vst.issue(Vs + (buf ^ 1) * C::TILEB, j0 + BN, t.k_len);
     }
-    if (j0 < nvis_w_max) {  // otherwise every key of this tile is masked for the whole wave
+    // the same copies one load at a time, K and V alternating (2 * PW loads = one per k-step); the sources are worked
+    // out unconditionally: a value defined under a branch would not stay in scalar registers
+    const void *pc_k = zp_uniform_ptr(kst.base + (int64_t)(j0 + BN) * kst.stride);
+    const void *pc_v = zp_uniform_ptr(vst.base + (int64_t)(j0 + BN) * vst.stride);
+    auto stage_piece = [&](auto n) {
+      constexpr int N = decltype(n)::value, i = N / 2;
+      static_assert(2 * PW == D / 16, "one copy per k-step");
+      if constexpr (N % 2 == 0)
+        zp_dma16_so(pc_k, kst.off[i], __builtin_amdgcn_readfirstlane(zp_lds_addr(Ks + (buf ^ 1) * C::TILEB) + (kst.w * PW + i) * 1024));
+      else
+        zp_dma16_so(pc_v, vst.off[i], __builtin_amdgcn_readfirstlane(zp_lds_addr(Vs + (buf ^ 1) * C::TILEB) + (vst.w * PW + i) * 1024));
+    };
+    if (compute) {
       const char *Kb = Ks + buf * C::TILEB;
       const char *Vb = Vs + buf * C::TILEB;
-      if (j0 + BN > nvis_w_min) fwd_tile<D, true>(Kb, Vb, qreg, o_acc, mc, l_sum, c_log2, j0, hi, nvis_lane, lo);
-      else fwd_tile<D, false>(Kb, Vb, qreg, o_acc, mc, l_sum, c_log2, j0, hi, nvis_lane, lo);
+      if (masked) fwd_tile<D, true, false>(Kb, Vb, qreg, o_acc, mc, l_sum, c_log2, j0, hi, nvis_lane, lo, stage_piece);
+      else if (fused) fwd_tile<D, false, true>(Kb, Vb, qreg, o_acc, mc, l_sum, c_log2, j0, hi, nvis_lane, lo, stage_piece);
+      else fwd_tile<D, false, false>(Kb, Vb, qreg, o_acc, mc, l_sum, c_log2, j0, hi, nvis_lane, lo, stage_piece);
     }
     zp_wait_async();
     __syncthreads();

@@ -2,6 +2,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
+#include <utility>
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
@@ -237,3 +239,13 @@ struct zp_lds_offsets {
     return zp_cat(zp_lds_read_tr(tile, tr_off[0][db] + o), zp_lds_read_tr(tile, tr_off[1][db] + o));
   }
 };
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in order
+template <class F, int... I>
+__device__ __forceinline__ void zp_static_for_impl(F &&f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void zp_static_for(F &&f) {
+  zp_static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
