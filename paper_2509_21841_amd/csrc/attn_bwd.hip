@@ -41,11 +41,7 @@ __device__ __forceinline__ void store_acc_rows(__bf16 *dst, const f32x16 (&acc)[
     }
 }
 
-#define ZP_SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
-#define ZP_SG_MFMA 0x008
-#define ZP_SG_VALU 0x002
-#define ZP_SG_TRANS 0x400
-#define ZP_SG_DSREAD 0x100
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
 // accumulate variant of store_acc_rows: dst is float, the scaled accumulator is added to what is there
 template <int D>
@@ -110,8 +106,6 @@ __device__ __forceinline__ void dq_half(const char *Kb, const char *Vb, int kb, 
       dq_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo.tr(Kb, kb, m, db), dsb[m], dq_acc[db], 0, 0, 0);
   __builtin_amdgcn_sched_barrier(0);
 }
-
-typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
 // Two neighbouring elements (registers r, r + 1 of the accumulators) of dS^T of a 32-key half, packed as bf16:
 // P^T = exp2(S^T c - LSE log2e), dS^T = P^T (dP^T - D)
@@ -349,144 +343,116 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
 // pipelined -- LDS operands are fetched a phase ahead, the exp/scale arithmetic of one block is interleaved
 // with the MFMAs of the other.
 
-// P = exp2(c * (q.k - LSE/scale)) and dS = P * (dO.v - D): the row terms were seeded into the accumulators.
-template <int D, bool MASK>
-__device__ __forceinline__ void dkdv_pds(const f32x16 &s, const f32x16 &dp, int qb, int hi, int qpos0, int kpos,
-                                         int qpos_end, float c_log2, bf16x8 (&pb)[2], bf16x8 (&dsb)[2]) {
-#pragma unroll
-  for (int r = 0; r < 16; r++) {
-    float pv = zp_exp2(s[r] * c_log2);
-    if (MASK) {
-      const int qpos = qpos0 + qb * 32 + 8 * (r >> 2) + 4 * hi + (r & 3);
-      if (qpos < kpos || qpos >= qpos_end) pv = 0.f;
-    }
-    pb[r >> 3][r & 7] = (__bf16)pv;
-    dsb[r >> 3][r & 7] = (__bf16)(pv * dp[r]);
+// Two neighbouring elements (registers r, r + 1 of the accumulators) of P and dS of a 32-query block, packed as bf16.
+// The accumulators were seeded with -LSE/scale and -D, so P = exp2(S c) and dS = P dP.
+template <bool MASK>
+__device__ __forceinline__ void dkdv_pair(const f32x16 &s, const f32x16 &dp, int r, int qb, int hi, int qpos0,
+                                          int kpos, int qpos_end, float c_log2, unsigned &p_pk, unsigned &ds_pk) {
+  float p0 = zp_exp2(s[r] * c_log2), p1 = zp_exp2(s[r + 1] * c_log2);
+  if (MASK) {
+    const int qpos = qpos0 + qb * 32 + 8 * (r >> 2) + 4 * hi + (r & 3);
+    if (qpos < kpos || qpos >= qpos_end) p0 = 0.f;
+    if (qpos + 1 < kpos || qpos + 1 >= qpos_end) p1 = 0.f;
   }
+  const bf16x2 pp = {(__bf16)p0, (__bf16)p1};
+  const bf16x2 dd = {(__bf16)(p0 * dp[r]), (__bf16)(p1 * dp[r + 1])};
+  p_pk = __builtin_bit_cast(unsigned, pp);
+  ds_pk = __builtin_bit_cast(unsigned, dd);
 }
 
-// One 64-query tile = two 32-query blocks, processed in phases with the LDS operands of the next phase
-// requested before the arithmetic of the current one:
-//   rows(0) | S,dP(0) | tr(0) requested, P,dS(0) | rows(1) requested, dV,dK(0) | S,dP(1) | tr(1), P,dS(1) | dV,dK(1)
-// `piece(integral_constant<int, n>)` is called after the n-th MFMA of the last phase (n = 0 .. 4 * D / 32 - 1):
-// the caller's asynchronous copies of a later tile are issued there, one load between two MFMAs, where nothing
-// else competes for the issue slot.
+// One 64-query tile = two 32-query blocks in four phases of D / 16 steps, two MFMAs per step:
+//   A: S,dP(0) | B: S,dP(1) || P,dS(0) | C: dV,dK(0) || P,dS(1) | D: dV,dK(1) || the caller's copies
+// A wave issues in order, so the overlap is written into the program order: every step is fenced, its two LDS
+// operands are requested two steps ahead (each phase thereby reads what its own MFMAs consume, 1/4 of the tile's
+// LDS traffic), and an empty volatile asm that takes the step's results as in/out operands pins its MFMAs and vector
+// arithmetic to the step. `piece(integral_constant<int, n>)` is called after the n-th MFMA of phase D
+// (n = 0 .. 4 * D / 32 - 1): the caller's asynchronous copies of a later tile are issued there, one load between two
+// MFMAs.
 template <int D, bool MASK, class Piece>
 __device__ __forceinline__ void dkdv_tile(const char *Qb, const char *Ob, const float *Lb, const float *Db,
                                           const bf16x8 (&kreg)[D / 16], const bf16x8 (&vreg)[D / 16],
                                           f32x16 (&dk_acc)[D / 32], f32x16 (&dv_acc)[D / 32], int qpos0, int kpos,
                                           int qpos_end, float c_log2, int hi, const zp_lds_offsets<D> &lo,
                                           Piece &&piece) {
-  constexpr int KK = D / 16, DB = D / 32;
-  bf16x8 aq[KK], ao[KK];
-  bf16x8 to[2][DB], tq[2][DB];
-  f32x16 s_seed[2], dp_seed[2];  // -LSE/scale and -D of the 16 query rows this lane holds, per block
-
-  auto load_seed = [&](int qb) {
+  constexpr int KK = D / 16, DB = D / 32, PPS = 8 / KK;  // steps per phase; pairs of P/dS elements per step
+  f32x16 s[2], dp[2];
+  auto load_seed = [&](int qb) {  // -LSE/scale and -D of the 16 query rows this lane holds
 #pragma unroll
     for (int b = 0; b < 4; b++) {
       const f32x4 l4 = *(const ZP_LDS f32x4 *)((const ZP_LDS char *)Lb + (qb * 32 + 8 * b + 4 * hi) * 4);
       const f32x4 d4 = *(const ZP_LDS f32x4 *)((const ZP_LDS char *)Db + (qb * 32 + 8 * b + 4 * hi) * 4);
 #pragma unroll
-      for (int c = 0; c < 4; c++) { s_seed[qb][4 * b + c] = l4[c]; dp_seed[qb][4 * b + c] = d4[c]; }
+      for (int c = 0; c < 4; c++) { s[qb][4 * b + c] = l4[c]; dp[qb][4 * b + c] = d4[c]; }
     }
   };
-  auto load_rows = [&](int qb) {
-#pragma unroll
-    for (int kk = 0; kk < KK; kk++) aq[kk] = lo.rows(Qb, qb, kk);
-#pragma unroll
-    for (int kk = 0; kk < KK; kk++) ao[kk] = lo.rows(Ob, qb, kk);
+  // operand pair of global step t (phase t / KK, step t % KK): rows of Q,dO for A and B, transposed pieces of dO,Q
+  // for C and D
+  bf16x8 x[4 * KK], y[4 * KK];
+  auto load_ops = [&](auto tt) {
+    constexpr int t = decltype(tt)::value, ph = t / KK, k = t % KK;
+    if constexpr (ph < 2) { x[t] = lo.rows(Qb, ph, k); y[t] = lo.rows(Ob, ph, k); }
+    else { x[t] = lo.tr(Ob, ph - 2, k / DB, k % DB); y[t] = lo.tr(Qb, ph - 2, k / DB, k % DB); }
   };
-  auto load_to = [&](int qb) {
-#pragma unroll
-    for (int m = 0; m < 2; m++)
-#pragma unroll
-      for (int db = 0; db < DB; db++) to[m][db] = lo.tr(Ob, qb, m, db);
-  };
-  auto load_tq = [&](int qb) {
-#pragma unroll
-    for (int m = 0; m < 2; m++)
-#pragma unroll
-      for (int db = 0; db < DB; db++) tq[m][db] = lo.tr(Qb, qb, m, db);
-  };
+  unsigned ppk[2][8], dpk[2][8];
 
-  // A: S,dP(0); the row operands and seeds of block 1 are requested meanwhile
   load_seed(0);
-  load_rows(0);
-  f32x16 s[2], dp[2];
-  bf16x8 pb[2][2], dsb[2][2];
-  bf16x8 aq1[KK], ao1[KK];
-  s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[0], kreg[0], s_seed[0], 0, 0, 0);
-  dp[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ao[0], vreg[0], dp_seed[0], 0, 0, 0);
-#pragma unroll
-  for (int kk = 1; kk < KK; kk++) {
-    s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[kk], kreg[kk], s[0], 0, 0, 0);
-    dp[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ao[kk], vreg[kk], dp[0], 0, 0, 0);
-  }
-  load_seed(1);
-#pragma unroll
-  for (int kk = 0; kk < KK; kk++) aq1[kk] = lo.rows(Qb, 1, kk);
-#pragma unroll
-  for (int kk = 0; kk < KK; kk++) ao1[kk] = lo.rows(Ob, 1, kk);
-#pragma unroll
-  for (int i = 0; i < 2 * KK; i++) { ZP_SGB(ZP_SG_MFMA, 1); ZP_SGB(ZP_SG_DSREAD, 2); }
-  __builtin_amdgcn_sched_barrier(0);
-
-  // B: S,dP(1) interleaved with P,dS(0); the transposed operands of block 0 are requested meanwhile
-  s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq1[0], kreg[0], s_seed[1], 0, 0, 0);
-  dp[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ao1[0], vreg[0], dp_seed[1], 0, 0, 0);
-#pragma unroll
-  for (int kk = 1; kk < KK; kk++) {
-    s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq1[kk], kreg[kk], s[1], 0, 0, 0);
-    dp[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ao1[kk], vreg[kk], dp[1], 0, 0, 0);
-  }
-  dkdv_pds<D, MASK>(s[0], dp[0], 0, hi, qpos0, kpos, qpos_end, c_log2, pb[0], dsb[0]);
-  load_to(0);
-  load_tq(0);
-#pragma unroll
-  for (int i = 0; i < 2 * KK; i++) { ZP_SGB(ZP_SG_MFMA, 1); ZP_SGB(ZP_SG_TRANS, 1); ZP_SGB(ZP_SG_VALU, 3); ZP_SGB(ZP_SG_DSREAD, 2); }
-  __builtin_amdgcn_sched_barrier(0);
-
-  // C: dV,dK(0) interleaved with P,dS(1); the transposed operands of block 1 are requested meanwhile
-  bf16x8 to1[2][DB], tq1[2][DB];
-#pragma unroll
-  for (int m = 0; m < 2; m++)
-#pragma unroll
-    for (int db = 0; db < DB; db++)
-      dv_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(to[m][db], pb[0][m], dv_acc[db], 0, 0, 0);
-#pragma unroll
-  for (int m = 0; m < 2; m++)
-#pragma unroll
-    for (int db = 0; db < DB; db++)
-      dk_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq[m][db], dsb[0][m], dk_acc[db], 0, 0, 0);
-  dkdv_pds<D, MASK>(s[1], dp[1], 1, hi, qpos0, kpos, qpos_end, c_log2, pb[1], dsb[1]);
-#pragma unroll
-  for (int m = 0; m < 2; m++)
-#pragma unroll
-    for (int db = 0; db < DB; db++) to1[m][db] = lo.tr(Ob, 1, m, db);
-#pragma unroll
-  for (int m = 0; m < 2; m++)
-#pragma unroll
-    for (int db = 0; db < DB; db++) tq1[m][db] = lo.tr(Qb, 1, m, db);
-#pragma unroll
-  for (int i = 0; i < 4 * DB; i++) { ZP_SGB(ZP_SG_MFMA, 1); ZP_SGB(ZP_SG_TRANS, 1); ZP_SGB(ZP_SG_VALU, 3); ZP_SGB(ZP_SG_DSREAD, 2); }
-  __builtin_amdgcn_sched_barrier(0);
-
-  // D: dV,dK(1), the caller's copies in between
-  zp_static_for<2 * DB>([&](auto n) {
-    constexpr int m = n.value / DB, db = n.value % DB;
-    dv_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(to1[m][db], pb[1][m], dv_acc[db], 0, 0, 0);
+  load_ops(std::integral_constant<int, 0>{});
+  load_ops(std::integral_constant<int, 1>{});
+  // A
+  zp_static_for<KK>([&](auto kk) {
+    constexpr int k = kk.value, t = k;
     __builtin_amdgcn_sched_barrier(0);
-    piece(n);
-    __builtin_amdgcn_sched_barrier(0);
+    s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x[t], kreg[k], s[0], 0, 0, 0);
+    dp[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(y[t], vreg[k], dp[0], 0, 0, 0);
+    load_ops(std::integral_constant<int, t + 2>{});
+    if constexpr (k == KK / 2) load_seed(1);
+    asm volatile("" : "+v"(s[0]), "+v"(dp[0]));
   });
-  zp_static_for<2 * DB>([&](auto n) {
-    constexpr int m = n.value / DB, db = n.value % DB;
-    dk_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq1[m][db], dsb[1][m], dk_acc[db], 0, 0, 0);
+  // B
+  zp_static_for<KK>([&](auto kk) {
+    constexpr int k = kk.value, t = KK + k;
     __builtin_amdgcn_sched_barrier(0);
-    piece(std::integral_constant<int, 2 * DB + n.value>{});
-    __builtin_amdgcn_sched_barrier(0);
+    s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x[t], kreg[k], s[1], 0, 0, 0);
+    dp[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(y[t], vreg[k], dp[1], 0, 0, 0);
+#pragma unroll
+    for (int q = 0; q < PPS; q++)
+      dkdv_pair<MASK>(s[0], dp[0], 2 * (PPS * k + q), 0, hi, qpos0, kpos, qpos_end, c_log2, ppk[0][PPS * k + q], dpk[0][PPS * k + q]);
+    load_ops(std::integral_constant<int, t + 2>{});
+    if constexpr (PPS == 1) asm volatile("" : "+v"(s[1]), "+v"(dp[1]), "+v"(ppk[0][k]), "+v"(dpk[0][k]));
+    else asm volatile("" : "+v"(s[1]), "+v"(dp[1]), "+v"(ppk[0][2 * k]), "+v"(dpk[0][2 * k]), "+v"(ppk[0][2 * k + 1]), "+v"(dpk[0][2 * k + 1]));
   });
+  auto pack4 = [](const unsigned (&v)[8], int m) {
+    return __builtin_bit_cast(bf16x8, (u32x4){v[4 * m], v[4 * m + 1], v[4 * m + 2], v[4 * m + 3]});
+  };
+  const bf16x8 pb0[2] = {pack4(ppk[0], 0), pack4(ppk[0], 1)}, dsb0[2] = {pack4(dpk[0], 0), pack4(dpk[0], 1)};
+  // C
+  zp_static_for<KK>([&](auto kk) {
+    constexpr int k = kk.value, t = 2 * KK + k, m = k / DB, db = k % DB;
+    __builtin_amdgcn_sched_barrier(0);
+    dv_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x[t], pb0[m], dv_acc[db], 0, 0, 0);
+    dk_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(y[t], dsb0[m], dk_acc[db], 0, 0, 0);
+#pragma unroll
+    for (int q = 0; q < PPS; q++)
+      dkdv_pair<MASK>(s[1], dp[1], 2 * (PPS * k + q), 1, hi, qpos0, kpos, qpos_end, c_log2, ppk[1][PPS * k + q], dpk[1][PPS * k + q]);
+    load_ops(std::integral_constant<int, t + 2>{});
+    if constexpr (PPS == 1) asm volatile("" : "+v"(dv_acc[db]), "+v"(dk_acc[db]), "+v"(ppk[1][k]), "+v"(dpk[1][k]));
+    else asm volatile("" : "+v"(dv_acc[db]), "+v"(dk_acc[db]), "+v"(ppk[1][2 * k]), "+v"(dpk[1][2 * k]), "+v"(ppk[1][2 * k + 1]), "+v"(dpk[1][2 * k + 1]));
+  });
+  const bf16x8 pb1[2] = {pack4(ppk[1], 0), pack4(ppk[1], 1)}, dsb1[2] = {pack4(dpk[1], 0), pack4(dpk[1], 1)};
+  // D
+  zp_static_for<KK>([&](auto kk) {
+    constexpr int k = kk.value, t = 3 * KK + k, m = k / DB, db = k % DB;
+    __builtin_amdgcn_sched_barrier(0);
+    dv_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x[t], pb1[m], dv_acc[db], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    piece(std::integral_constant<int, 2 * k>{});
+    __builtin_amdgcn_sched_barrier(0);
+    dk_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(y[t], dsb1[m], dk_acc[db], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    piece(std::integral_constant<int, 2 * k + 1>{});
+    if constexpr (k + 2 < KK) load_ops(std::integral_constant<int, t + 2>{});
+  });
+  __builtin_amdgcn_sched_barrier(0);
 }
 
 template <int D>
