@@ -284,6 +284,25 @@ def test_bwd_custom_scale_and_deterministic():
         assert torch.equal(x.view(torch.int16), y.view(torch.int16))
 
 
+def test_bwd_closed_forms_on_device():
+    """Q = K = 0: the probabilities are uniform over the visible keys, so dQ and dK vanish exactly and
+    dV_j = sum over the heads of the group and over queries i >= j of dO_i / (i + 1)."""
+    lengths = [1, 300]
+    Hq, Hkv, d = 4, 2, 128
+    (q, k, v, do), cu = make(lengths, Hq, Hkv, d, 37, with_dout=True)
+    q = torch.zeros_like(q); k = torch.zeros_like(k)
+    o, lse = B.varlen_attn_fwd(q, k, v, cu)
+    dq, dk, dv = B.varlen_attn_bwd(do, q, k, v, o, lse, cu)
+    torch.cuda.synchronize()
+    assert not dq.any() and not dk.any()
+    dof = widen(do)
+    w = dof[1:] / np.arange(1, 301)[:, None, None]                       # dO_i / (i + 1), i = 0..299
+    suffix = np.cumsum(w[::-1], axis=0)[::-1]                            # sum over i >= j
+    ref = suffix.reshape(300, Hkv, Hq // Hkv, d).sum(axis=2)
+    assert_close("dV", widen(dv)[1:], ref)
+    assert_close("dV of the length-1 sequence", widen(dv)[:1], dof[:1].reshape(1, Hkv, Hq // Hkv, d).sum(axis=2))
+
+
 # ---- chunked backward --------------------------------------------------------------------------------
 def run_chunked_bwd(lengths, which, C, Hq, Hkv, d, seed, scale=0.0):
     """Ring rounds of the chunked sequence `which` (Sec. 3.2): each round is one call that adds its pairs'
