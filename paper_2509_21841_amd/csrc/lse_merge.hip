@@ -1,7 +1,8 @@
 // Online-softmax combination of partial attention results (Sec. 3.2, ring attention rounds):
 //   LSE = log sum_p exp(LSE_p),  O = sum_p exp(LSE_p - LSE) O_p.
 // Elementwise and HBM-bound: each lane owns 4 consecutive head-dim elements of one (row, head), reads the
-// n_parts partial LSEs (broadcast within the row) and n_parts float4, writes 4 bf16.
+// n_parts partial LSEs (broadcast within the row) and n_parts float4, writes 4 bf16; two such items are in flight
+// per lane.
 #include "zp_common.h"
 
 extern "C" void zp_prof_begin(const char *name, hipStream_t stream);
@@ -15,7 +16,9 @@ struct zp_merge_dev {
 struct zp_merge_item { int32_t merge, row0; };  // a band of up to MERGE_ROWS rows of one merge
 
 namespace {
-constexpr int MERGE_NT = 512;
+// picked by a sweep over {256, 512, 1024} threads x {4, 8, 16} rows x {1, 2, 4} items in flight per lane (two where the
+// registers of 1024 threads allow it, i.e. up to 8 parts)
+constexpr int MERGE_NT = 1024;
 constexpr int MERGE_ROWS = 8;
 
 // MAXP: compile-time bound of n_parts for this launch (the host picks the smallest of 4, 8, 16 that covers every
@@ -33,39 +36,52 @@ __global__ __launch_bounds__(MERGE_NT) void lse_merge_kernel(const float *__rest
   const int d4 = d >> 2;
   const int per_row = Hq * d4;
   const int total = rows * per_row;
-  for (int w = threadIdx.x; w < total; w += MERGE_NT) {
-    const int r = w / per_row, rem = w - r * per_row;
-    const int h = rem / d4, c4 = rem - h * d4;
-    const int rr = it.row0 + r;
-    // all loads of the item are issued before any arithmetic: n_parts LSEs and n_parts float4 in flight
-    float lp[MAXP];
-    f32x4 v[MAXP];
+  constexpr int ILP = MAXP <= 8 ? 2 : 1;
+  // ILP items per lane and trip: every load of all of them is issued before any arithmetic
+  for (int w0 = threadIdx.x; w0 < total; w0 += ILP * MERGE_NT) {
+    float lp[ILP][MAXP];
+    f32x4 v[ILP][MAXP];
+    int rr[ILP], h[ILP], c4[ILP];
 #pragma unroll
-    for (int p = 0; p < MAXP; p++)
-      if (p < mg.n_parts) {
-        lp[p] = lse_part[(int64_t)h * part_rows + mg.part_row0[p] + rr];
-        v[p] = __builtin_nontemporal_load((const f32x4 *)(o_part + ((int64_t)(mg.part_row0[p] + rr) * Hq + h) * d) + c4);
+    for (int u = 0; u < ILP; u++) {
+      const int w = w0 + u * MERGE_NT;
+      if (w < total) {
+        const int r = w / per_row, rem = w - r * per_row;
+        h[u] = rem / d4; c4[u] = rem - h[u] * d4; rr[u] = it.row0 + r;
+#pragma unroll
+        for (int p = 0; p < MAXP; p++)
+          if (p < mg.n_parts) {
+            lp[u][p] = lse_part[(int64_t)h[u] * part_rows + mg.part_row0[p] + rr[u]];
+            v[u][p] = __builtin_nontemporal_load((const f32x4 *)(o_part + ((int64_t)(mg.part_row0[p] + rr[u]) * Hq + h[u]) * d) + c4[u]);
+          }
       }
-    float mx = -INFINITY;
-#pragma unroll
-    for (int p = 0; p < MAXP; p++)
-      if (p < mg.n_parts) mx = fmaxf(mx, lp[p]);
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    float L = -INFINITY;
-    if (mx != -INFINITY) {
-      float sum = 0.f;
-#pragma unroll
-      for (int p = 0; p < MAXP; p++)
-        if (p < mg.n_parts) sum += __expf(lp[p] - mx);
-      L = mx + __logf(sum);
-#pragma unroll
-      for (int p = 0; p < MAXP; p++)
-        if (p < mg.n_parts && lp[p] != -INFINITY) acc += __expf(lp[p] - L) * v[p];
     }
-    const int64_t t = (int64_t)mg.out_tok0 + rr;
-    bf16x4 ob = {(__bf16)acc[0], (__bf16)acc[1], (__bf16)acc[2], (__bf16)acc[3]};
-    *(bf16x4 *)(o + t * o_stride + (int64_t)h * d + 4 * c4) = ob;
-    if (c4 == 0) lse[(int64_t)h * T + t] = L;
+#pragma unroll
+    for (int u = 0; u < ILP; u++) {
+      const int w = w0 + u * MERGE_NT;
+      if (w < total) {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int p = 0; p < MAXP; p++)
+          if (p < mg.n_parts) mx = fmaxf(mx, lp[u][p]);
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        float L = -INFINITY;
+        if (mx != -INFINITY) {
+          float sum = 0.f;
+#pragma unroll
+          for (int p = 0; p < MAXP; p++)
+            if (p < mg.n_parts) sum += __expf(lp[u][p] - mx);
+          L = mx + __logf(sum);
+#pragma unroll
+          for (int p = 0; p < MAXP; p++)
+            if (p < mg.n_parts && lp[u][p] != -INFINITY) acc += __expf(lp[u][p] - L) * v[u][p];
+        }
+        const int64_t t = (int64_t)mg.out_tok0 + rr[u];
+        bf16x4 ob = {(__bf16)acc[0], (__bf16)acc[1], (__bf16)acc[2], (__bf16)acc[3]};
+        __builtin_nontemporal_store(ob, (bf16x4 *)(o + t * o_stride + (int64_t)h[u] * d + 4 * c4[u]));
+        if (c4[u] == 0) lse[(int64_t)h[u] * T + t] = L;
+      }
+    }
   }
 }
 }  // namespace
