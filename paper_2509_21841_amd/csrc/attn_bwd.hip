@@ -58,8 +58,7 @@ __device__ __forceinline__ void add_acc_rows(float *dst, const f32x16 (&acc)[D /
 }
 
 // ------------------------------------------------------------------------------------------- dQ
-// One 32-key half of a K/V tile for one wave: S^T and dP^T chains, dS^T, then dQ^T += K^T dS^T (head dimension 64;
-// for 128 see dq_tile below).
+// One 32-key half of a K/V tile for one wave: S^T and dP^T chains, dS^T, then dQ^T += K^T dS^T.
 // `piece(integral_constant<int, kk>)` is called once per 16-wide k-step of the chains when PIECES is set, in program
 // order between the LDS operand reads of step kk and those of step kk + 1: the caller issues one asynchronous copy
 // of the next tile there. The copies are ordered against every LDS access, the reads are pinned to the MFMAs by the
@@ -107,85 +106,12 @@ __device__ __forceinline__ void dq_half(const char *Kb, const char *Vb, int kb, 
   __builtin_amdgcn_sched_barrier(0);
 }
 
-// Two neighbouring elements (registers r, r + 1 of the accumulators) of dS^T of a 32-key half, packed as bf16:
-// P^T = exp2(S^T c - LSE log2e), dS^T = P^T (dP^T - D)
-template <bool MASK>
-__device__ __forceinline__ unsigned dq_ds_pair(const f32x16 &s, const f32x16 &dp, int r, int kb, float c_log2,
-                                               float lse2, int j0, int hi, int nvis_lane) {
-  float p0 = zp_exp2(__builtin_fmaf(s[r], c_log2, -lse2));
-  float p1 = zp_exp2(__builtin_fmaf(s[r + 1], c_log2, -lse2));
-  if (MASK) {
-    const int j = j0 + kb * 32 + 8 * (r >> 2) + 4 * hi + (r & 3);
-    if (j >= nvis_lane) p0 = 0.f;
-    if (j + 1 >= nvis_lane) p1 = 0.f;
-  }
-  const bf16x2 pk = {(__bf16)(p0 * dp[r]), (__bf16)(p1 * dp[r + 1])};
-  return __builtin_bit_cast(unsigned, pk);
-}
-
-// One 64-key tile for one wave in four phases, the vector arithmetic of one 32-key half under the MFMAs of the other:
-//   A: S,dP chains(0), copies | B: S,dP chains(1) || dS(0) | C: dQ(0) || dS(1) | D: dQ(1)
-// Every phase is cut into fenced steps (a wave issues in order, so the overlap has to be in the program order); an
-// empty volatile asm that takes a step's results as in/out operands pins its MFMAs and arithmetic to the step.
-template <int D, bool MASK, bool PIECES, class Piece>
-__device__ __forceinline__ void dq_tile(const char *Kb, const char *Vb, const bf16x8 (&qreg)[D / 16],
-                                        const bf16x8 (&doreg)[D / 16], f32x16 (&dq_acc)[D / 32], float c_log2,
-                                        float lse2, const f32x16 &negD, int j0, int hi, int nvis_lane,
-                                        const zp_lds_offsets<D> &lo, Piece &&piece) {
-  constexpr int KK = D / 16, DB = D / 32;
-  static_assert(KK == 8 && DB == 4, "step counts below are written for d = 128");
-  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  f32x16 s0 = zero, dp0 = negD, s1 = zero, dp1 = negD;
-  bf16x8 ka[KK], va[KK], ka1[KK], va1[KK];
-  // A
-  ka[0] = lo.rows(Kb, 0, 0); va[0] = lo.rows(Vb, 0, 0);
-  ka[1] = lo.rows(Kb, 0, 1); va[1] = lo.rows(Vb, 0, 1);
-  zp_static_for<KK>([&](auto kk) {
-    constexpr int k = kk.value;
-    __builtin_amdgcn_sched_barrier(0);
-    s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[k], qreg[k], s0, 0, 0, 0);
-    dp0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[k], doreg[k], dp0, 0, 0, 0);
-    if constexpr (k + 2 < KK) { ka[k + 2] = lo.rows(Kb, 0, k + 2); va[k + 2] = lo.rows(Vb, 0, k + 2); }
-    else { ka1[k + 2 - KK] = lo.rows(Kb, 1, k + 2 - KK); va1[k + 2 - KK] = lo.rows(Vb, 1, k + 2 - KK); }
-    if constexpr (PIECES) piece(kk);
-    asm volatile("" : "+v"(s0), "+v"(dp0));
-  });
-  // B
-  unsigned pk0[8], pk1[8];
-  bf16x8 kt0[2 * DB], kt1[2 * DB];
-  zp_static_for<KK>([&](auto kk) {
-    constexpr int k = kk.value;
-    __builtin_amdgcn_sched_barrier(0);
-    s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka1[k], qreg[k], s1, 0, 0, 0);
-    dp1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va1[k], doreg[k], dp1, 0, 0, 0);
-    pk0[k] = dq_ds_pair<MASK>(s0, dp0, 2 * k, 0, c_log2, lse2, j0, hi, nvis_lane);
-    if constexpr (k + 2 < KK) { ka1[k + 2] = lo.rows(Kb, 1, k + 2); va1[k + 2] = lo.rows(Vb, 1, k + 2); }
-    kt0[k] = lo.tr(Kb, 0, k / DB, k % DB);
-    asm volatile("" : "+v"(s1), "+v"(dp1), "+v"(pk0[k]));
-  });
-  const bf16x8 dsb0[2] = {__builtin_bit_cast(bf16x8, (u32x4){pk0[0], pk0[1], pk0[2], pk0[3]}),
-                          __builtin_bit_cast(bf16x8, (u32x4){pk0[4], pk0[5], pk0[6], pk0[7]})};
-  // C
-  zp_static_for<2 * DB>([&](auto ii) {
-    constexpr int i = ii.value, m = i / DB, db = i % DB;
-    __builtin_amdgcn_sched_barrier(0);
-    dq_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt0[i], dsb0[m], dq_acc[db], 0, 0, 0);
-    pk1[i] = dq_ds_pair<MASK>(s1, dp1, 2 * i, 1, c_log2, lse2, j0, hi, nvis_lane);
-    kt1[i] = lo.tr(Kb, 1, m, db);
-    asm volatile("" : "+v"(dq_acc[db]), "+v"(pk1[i]));
-  });
-  const bf16x8 dsb1[2] = {__builtin_bit_cast(bf16x8, (u32x4){pk1[0], pk1[1], pk1[2], pk1[3]}),
-                          __builtin_bit_cast(bf16x8, (u32x4){pk1[4], pk1[5], pk1[6], pk1[7]})};
-  __builtin_amdgcn_sched_barrier(0);
-  // D
-#pragma unroll
-  for (int i = 0; i < 2 * DB; i++)
-    dq_acc[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt1[i], dsb1[i / DB], dq_acc[i % DB], 0, 0, 0);
-  __builtin_amdgcn_sched_barrier(0);
-}
-
+// Two waves per SIMD (two workgroups of four waves per CU, 64 KB of LDS each). An MFMA takes about 20 cycles of the
+// issuing wave's vector issue time, and a wave issues its LDS, scalar and wait instructions one after the other as
+// well; with a second wave on the SIMD all of that runs under the other wave's MFMAs. Working through a tile in two
+// 32-key halves keeps the wave within the 256 registers this needs.
 template <int D>
-__global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void attn_bwd_dq_kernel(zp_bwd_params p) {
+__global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dq_kernel(zp_bwd_params p) {
   constexpr int TILEB = 64 * D * 2;
   constexpr int LOADS = 2 * zp_stager<D>::LOADS;  // async loads one wave issues per staged K/V tile pair
   extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -305,11 +231,7 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) 
     if (compute) {
       const char *Kb = Ks + buf * TILEB;
       const char *Vb = Vs + buf * TILEB;
-      if constexpr (D == 128) {
-        if (masked) dq_tile<D, true, false>(Kb, Vb, qreg, doreg, dq_acc, c_log2, lse2, negD, j0, hi, nvis_lane, lo, stage_piece);
-        else if (fused) dq_tile<D, false, true>(Kb, Vb, qreg, doreg, dq_acc, c_log2, lse2, negD, j0, hi, nvis_lane, lo, stage_piece);
-        else dq_tile<D, false, false>(Kb, Vb, qreg, doreg, dq_acc, c_log2, lse2, negD, j0, hi, nvis_lane, lo, stage_piece);
-      } else if (masked) {
+      if (masked) {
         dq_half<D, true, false>(Kb, Vb, 0, qreg, doreg, dq_acc, c_log2, lse2, negD, j0, hi, nvis_lane, lo, stage_piece);
         dq_half<D, true, false>(Kb, Vb, 1, qreg, doreg, dq_acc, c_log2, lse2, negD, j0, hi, nvis_lane, lo, stage_piece);
       } else if (fused) {
