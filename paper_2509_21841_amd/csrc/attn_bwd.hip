@@ -378,7 +378,7 @@ __device__ __forceinline__ void dkdv_tile(const char *Qb, const char *Ob, const 
 }
 
 template <int D>
-__global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void attn_bwd_dkdv_kernel(zp_bwd_params p) {
+__global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(D == 64 ? 2 : 1, D == 64 ? 2 : 1))) void attn_bwd_dkdv_kernel(zp_bwd_params p) {
   constexpr int TILEB = 64 * D * 2;
   constexpr int NBUF = 4;                       // tiles are fetched three iterations ahead
   constexpr int LOADS = 2 * (TILEB / 4096) + 2; // async loads one wave issues per staged tile
