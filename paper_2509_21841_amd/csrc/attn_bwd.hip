@@ -65,7 +65,7 @@ __device__ __forceinline__ void add_acc_rows(float *dst, const f32x16 (&acc)[D /
 // scheduling groups below, so the copies end up one per MFMA pair -- far enough apart that none waits for the
 // address unit behind the copies of the other three waves.
 template <int D, bool MASK, bool PIECES, class Piece>
-__device__ __forceinline__ void dq_half(const char *Kb, const char *Vb, int kb, const bf16x8 (&qreg)[D / 16],
+__device__ __forceinline__ void dq_half(int Kb, int Vb, int kb, const bf16x8 (&qreg)[D / 16],
                                         const bf16x8 (&doreg)[D / 16], f32x16 (&dq_acc)[D / 32], float c_log2,
                                         float lse2, const f32x16 &negD, int j0, int hi, int nvis_lane,
                                         const zp_lds_offsets<D> &lo, Piece &&piece) {
@@ -77,14 +77,14 @@ __device__ __forceinline__ void dq_half(const char *Kb, const char *Vb, int kb, 
   // copies keep their distance
   f32x16 s = zero, dp = negD;
   bf16x8 ka[KK], va[KK];
-  ka[0] = lo.rows(Kb, kb, 0); va[0] = lo.rows(Vb, kb, 0);
-  ka[1] = lo.rows(Kb, kb, 1); va[1] = lo.rows(Vb, kb, 1);
+  ka[0] = lo.rows_at(Kb, kb, 0); va[0] = lo.rows_at(Vb, kb, 0);
+  ka[1] = lo.rows_at(Kb, kb, 1); va[1] = lo.rows_at(Vb, kb, 1);
   zp_static_for<KK>([&](auto kk) {
     constexpr int k = kk.value;
     __builtin_amdgcn_sched_barrier(0);
     s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[k], qreg[k], s, 0, 0, 0);
     dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[k], doreg[k], dp, 0, 0, 0);
-    if constexpr (k + 2 < KK) { ka[k + 2] = lo.rows(Kb, kb, k + 2); va[k + 2] = lo.rows(Vb, kb, k + 2); }
+    if constexpr (k + 2 < KK) { ka[k + 2] = lo.rows_at(Kb, kb, k + 2); va[k + 2] = lo.rows_at(Vb, kb, k + 2); }
     if constexpr (PIECES) piece(kk);
   });
   __builtin_amdgcn_sched_barrier(0);
@@ -102,7 +102,7 @@ __device__ __forceinline__ void dq_half(const char *Kb, const char *Vb, int kb, 
   for (int m = 0; m < 2; m++)
 #pragma unroll
     for (int db = 0; db < DB; db++)
-      dq_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo.tr(Kb, kb, m, db), dsb[m], dq_acc[db], 0, 0, 0);
+      dq_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo.tr_at(Kb, kb, m, db), dsb[m], dq_acc[db], 0, 0, 0);
   __builtin_amdgcn_sched_barrier(0);
 }
 
@@ -143,7 +143,7 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) 
   kst.init(p.k + (int64_t)t.k_tok0 * p.k_stride + (int64_t)g * D, p.k_stride, tid);
   vst.init(p.v + (int64_t)t.k_tok0 * p.v_stride + (int64_t)g * D, p.v_stride, tid);
   zp_lds_offsets<D> lo;
-  lo.init(lane);
+  lo.init_abs(lane, smem);
 
   // Row operands first, the first tile copy right behind them (the two memory latencies overlap), their first use
   // after that. The explicit wait before the first barrier covers all of it and tells the compiler that the register
@@ -229,8 +229,7 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) 
         zp_dma16_so(pc_v, vst.off[i], __builtin_amdgcn_readfirstlane(zp_lds_addr(Vs + (buf ^ 1) * TILEB) + (vst.w * PW + i) * 1024));
     };
     if (compute) {
-      const char *Kb = Ks + buf * TILEB;
-      const char *Vb = Vs + buf * TILEB;
+      constexpr int Kb = buf * TILEB, Vb = (2 + buf) * TILEB;  // byte offsets of the tiles from smem
       if (masked) {
         dq_half<D, true, false>(Kb, Vb, 0, qreg, doreg, dq_acc, c_log2, lse2, negD, j0, hi, nvis_lane, lo, stage_piece);
         dq_half<D, true, false>(Kb, Vb, 1, qreg, doreg, dq_acc, c_log2, lse2, negD, j0, hi, nvis_lane, lo, stage_piece);

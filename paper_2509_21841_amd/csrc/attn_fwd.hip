@@ -30,7 +30,7 @@ struct FwdCfg {
 // -- far enough that none waits for the address unit behind the copies of the other waves, which is what issuing
 // them back to back in front of the tile costs.
 template <int D, bool MASK, bool PIECES, class Piece>
-__device__ __forceinline__ void fwd_tile(const char *Kb, const char *Vb, const bf16x8 (&qreg)[D / 16],
+__device__ __forceinline__ void fwd_tile(int Kb, int Vb, const bf16x8 (&qreg)[D / 16],
                                          f32x16 (&o_acc)[D / 32], float &mc, float &l_sum, float c_log2, int j0,
                                          int hi, int nvis_lane, const zp_lds_offsets<D> &lo, Piece &&piece) {
   constexpr int KK = D / 16, DB = D / 32;
@@ -39,22 +39,22 @@ __device__ __forceinline__ void fwd_tile(const char *Kb, const char *Vb, const b
   if constexpr (PIECES) {
     // the K row operands stay two k-steps ahead of the MFMAs that use them
     bf16x8 k0[KK], k1[KK];
-    k0[0] = lo.rows(Kb, 0, 0); k1[0] = lo.rows(Kb, 1, 0);
-    k0[1] = lo.rows(Kb, 0, 1); k1[1] = lo.rows(Kb, 1, 1);
+    k0[0] = lo.rows_at(Kb, 0, 0); k1[0] = lo.rows_at(Kb, 1, 0);
+    k0[1] = lo.rows_at(Kb, 0, 1); k1[1] = lo.rows_at(Kb, 1, 1);
     zp_static_for<KK>([&](auto kk) {
       constexpr int k = kk.value;
       __builtin_amdgcn_sched_barrier(0);
       s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0[k], qreg[k], s0, 0, 0, 0);
       s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1[k], qreg[k], s1, 0, 0, 0);
-      if constexpr (k + 2 < KK) { k0[k + 2] = lo.rows(Kb, 0, k + 2); k1[k + 2] = lo.rows(Kb, 1, k + 2); }
+      if constexpr (k + 2 < KK) { k0[k + 2] = lo.rows_at(Kb, 0, k + 2); k1[k + 2] = lo.rows_at(Kb, 1, k + 2); }
       piece(kk);
     });
     __builtin_amdgcn_sched_barrier(0);
   } else {
 #pragma unroll
     for (int kk = 0; kk < KK; kk++) {
-      s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo.rows(Kb, 0, kk), qreg[kk], s0, 0, 0, 0);
-      s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo.rows(Kb, 1, kk), qreg[kk], s1, 0, 0, 0);
+      s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo.rows_at(Kb, 0, kk), qreg[kk], s0, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo.rows_at(Kb, 1, kk), qreg[kk], s1, 0, 0, 0);
     }
   }
   if (MASK) {
@@ -109,7 +109,7 @@ __device__ __forceinline__ void fwd_tile(const char *Kb, const char *Vb, const b
     for (int m = 0; m < 2; m++)
 #pragma unroll
       for (int db = 0; db < DB; db++)
-        o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo.tr(Vb, kb, m, db), pb[kb][m], o_acc[db], 0, 0, 0);
+        o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo.tr_at(Vb, kb, m, db), pb[kb][m], o_acc[db], 0, 0, 0);
 }
 
 template <int D, int NW, bool PARTIAL>
@@ -158,7 +158,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   kst.init(p.k + (int64_t)t.k_tok0 * p.k_stride + (int64_t)g * D, p.k_stride, tid);
   vst.init(p.v + (int64_t)t.k_tok0 * p.v_stride + (int64_t)g * D, p.v_stride, tid);
   zp_lds_offsets<D> lo;
-  lo.init(lane);
+  lo.init_abs(lane, smem);
 
   f32x16 o_acc[D / 32];
 #pragma unroll
@@ -204,8 +204,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
         zp_dma16_so(pc_v, vst.off[i], __builtin_amdgcn_readfirstlane(zp_lds_addr(Vs + (buf ^ 1) * C::TILEB) + (vst.w * PW + i) * 1024));
     };
     if (compute) {
-      const char *Kb = Ks + buf * C::TILEB;
-      const char *Vb = Vs + buf * C::TILEB;
+      constexpr int Kb = buf * C::TILEB, Vb = (2 + buf) * C::TILEB;  // byte offsets of the tiles from smem
       if (masked) fwd_tile<D, true, false>(Kb, Vb, qreg, o_acc, mc, l_sum, c_log2, j0, hi, nvis_lane, lo, stage_piece);
       else if (fused) fwd_tile<D, false, true>(Kb, Vb, qreg, o_acc, mc, l_sum, c_log2, j0, hi, nvis_lane, lo, stage_piece);
       else fwd_tile<D, false, false>(Kb, Vb, qreg, o_acc, mc, l_sum, c_log2, j0, hi, nvis_lane, lo, stage_piece);

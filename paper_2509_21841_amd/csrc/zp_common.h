@@ -230,6 +230,34 @@ struct zp_lds_offsets {
 #pragma unroll
       for (int db = 0; db < D / 32; db++) tr_off[j][db] = zp_swz_col<D>(8 * j + trow, db * 32 + tcol);
   }
+  // Absolute form: the lane's offsets include the LDS address of `base` from then on, and the *_at readers take a
+  // tile's byte offset from `base` -- with a compile-time offset every read is a register plus an immediate (the
+  // pointer form costs one vector add per read for the base, which the compiler only knows as a relocation).
+  __device__ __forceinline__ void init_abs(int lane, const char *base) {
+    init(lane);
+    const int b = (int)(unsigned)(unsigned long long)(const ZP_LDS char *)base;
+#pragma unroll
+    for (int kk = 0; kk < D / 16; kk++) {
+      row_off[kk] += b;
+      asm volatile("" : "+v"(row_off[kk]));  // opaque from here on: the compiler would otherwise split the sum again and redo the add at every read
+    }
+#pragma unroll
+    for (int j = 0; j < 2; j++)
+#pragma unroll
+      for (int db = 0; db < D / 32; db++) {
+        tr_off[j][db] += b;
+        asm volatile("" : "+v"(tr_off[j][db]));
+      }
+  }
+  __device__ __forceinline__ bf16x8 rows_at(int tile_off, int kb, int kk) const {
+    return *(const ZP_LDS bf16x8 *)(unsigned long long)(unsigned)(row_off[kk] + tile_off + kb * 32 * ROWB);
+  }
+  __device__ __forceinline__ bf16x8 tr_at(int tile_off, int kb, int m, int db) const {
+    const int o = tile_off + (kb * 32 + m * 16) * ROWB;
+    s16x4 u0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ZP_LDS s16x4 *)(unsigned long long)(unsigned)(tr_off[0][db] + o));
+    s16x4 u1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ZP_LDS s16x4 *)(unsigned long long)(unsigned)(tr_off[1][db] + o));
+    return zp_cat(__builtin_bit_cast(bf16x4, u0), __builtin_bit_cast(bf16x4, u1));
+  }
   // the swizzle depends on row % 16 only (D = 128) / row % 8 (D = 64), so blocks of 32 and 16 rows shift by a constant
   __device__ __forceinline__ bf16x8 rows(const char *tile, int kb, int kk) const {
     return zp_lds_read16(tile, row_off[kk] + kb * 32 * ROWB);
