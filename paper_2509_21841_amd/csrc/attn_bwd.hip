@@ -59,11 +59,10 @@ __device__ __forceinline__ void add_acc_rows(float *dst, const f32x16 (&acc)[D /
 
 // ------------------------------------------------------------------------------------------- dQ
 // One 32-key half of a K/V tile for one wave: S^T and dP^T chains, dS^T, then dQ^T += K^T dS^T.
-// `piece(integral_constant<int, kk>)` is called once per 16-wide k-step of the chains when PIECES is set, in program
-// order between the LDS operand reads of step kk and those of step kk + 1: the caller issues one asynchronous copy
-// of the next tile there. The copies are ordered against every LDS access, the reads are pinned to the MFMAs by the
-// scheduling groups below, so the copies end up one per MFMA pair -- far enough apart that none waits for the
-// address unit behind the copies of the other three waves.
+// `piece(integral_constant<int, kk>)` is called once per 16-wide k-step of the chains when PIECES is set: the caller
+// issues one asynchronous copy of the next tile there. Every step is fenced and the copies are ordered against every
+// LDS access, so they end up one per MFMA pair -- far enough apart that none waits for the address unit behind the
+// copies of the other waves. Kb, Vb: byte offsets of the K and V tile from the base the lane offsets carry.
 template <int D, bool MASK, bool PIECES, class Piece>
 __device__ __forceinline__ void dq_half(int Kb, int Vb, int kb, const bf16x8 (&qreg)[D / 16],
                                         const bf16x8 (&doreg)[D / 16], f32x16 (&dq_acc)[D / 32], float c_log2,
