@@ -13,9 +13,6 @@
 namespace {
 
 constexpr int BN = 64;  // keys per LDS tile
-#define ZP_SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
-#define ZP_SG_MFMA 0x008
-#define ZP_SG_DSREAD 0x100
 
 template <int D, int NW>
 struct FwdCfg {
@@ -24,7 +21,8 @@ struct FwdCfg {
   static constexpr int TILEB = BN * D * 2;  // bytes per K (or V) tile
 };
 
-// One 64-key tile for one wave of 32 query rows.
+// One 64-key tile for one wave of 32 query rows. Kb, Vb: byte offsets of the K and V tile from the LDS base that
+// the lane offsets in `lo` carry (compile-time at the call sites, so every read is a register plus an immediate).
 // With PIECES, `piece(integral_constant<int, kk>)` is called once per 16-wide k-step of the score MFMAs: the caller
 // issues one asynchronous copy of the next tile there. The steps are fenced, so the copies stay one MFMA pair apart
 // -- far enough that none waits for the address unit behind the copies of the other waves, which is what issuing
