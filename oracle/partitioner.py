@@ -11,12 +11,18 @@ Readings where the listing is silent:
    G devices (G = k*P for z2, G = min(P, ceil(|s|^2 / c_avg)) for z1), is cut into 2G equal-length chunks
    (chunk c = [floor(c|s|/2G), floor((c+1)|s|/2G)) ) and ring rank r holds chunks r and 2G-1-r (Sec. 3.2);
  * a z1 sequence with G = 1 is placed whole; round-robin continues across the sequences of z1;
- * loads compared in the greedy steps are token counts, as the listing writes them.
+ * loads compared in the greedy steps are token counts, as the listing writes them;
+ * the budgets s_avg and c_avg are rationals: the ceilings are taken exactly (integer arithmetic), so that a
+   sequence of exactly k budgets gets k buckets whatever a floating-point quotient would round to.
 Returns placements: dicts {seq, zone, ring, rank, node, device, tokens}.
 """
 from __future__ import annotations
 
-import math
+
+
+def ceil_ratio(num: int, den: int) -> int:
+    """ceil(num / den) in exact integer arithmetic; an all-zero zone (den = 0) asks for one bucket."""
+    return -(-num // den) if den > 0 else 1
 
 
 def ring_tokens(length: int, G: int, r: int) -> int:
@@ -36,9 +42,9 @@ def inter_node(lengths, P: int, N: int, L: int):
         z01 = [s for s in order if lengths[s] < s1]
         z2 = [s for s in order if lengths[s] >= s1]
         if z2:
-            s_avg = sum(lengths[s] for s in z2) / N
+            z2_tokens = sum(lengths[s] for s in z2)          # s_avg = z2_tokens / N, kept as an exact fraction
             for s in z2:
-                k = min(N, math.ceil(lengths[s] / s_avg))
+                k = max(1, min(N, ceil_ratio(lengths[s] * N, z2_tokens)))  # ceil(|s| / s_avg); an empty sequence still gets a bucket
                 nodes = sorted(range(N), key=lambda n: (load[n], n))[:k]
                 for m, n in enumerate(sorted(nodes)):
                     node_buckets[n].append(("frag", s, k, m))
@@ -73,10 +79,10 @@ def intra_node(lengths, bucket, P: int, L: int, node: int):
         z0 = [s for s in z01 if lengths[s] < s0]
         z1 = [s for s in z01 if lengths[s] >= s0]
         if z1:
-            c_avg = sum(lengths[s] ** 2 for s in z1) / P
+            z1_cost = sum(lengths[s] ** 2 for s in z1)       # c_avg = z1_cost / P, kept as an exact fraction
             nxt = 0
             for s in z1:
-                G = min(P, math.ceil(lengths[s] ** 2 / c_avg))
+                G = max(1, min(P, ceil_ratio(lengths[s] ** 2 * P, z1_cost)))  # ceil(|s|^2 / c_avg); an empty sequence still gets a bucket
                 for r in range(G):
                     p = nxt % P
                     nxt += 1

@@ -22,10 +22,11 @@ inline int32_t ring_share(int64_t len, int64_t G, int64_t r) {
   return (int32_t)((chunk_bound(len, r + 1, G) - chunk_bound(len, r, G)) +
                    (chunk_bound(len, 2 * G - r, G) - chunk_bound(len, 2 * G - 1 - r, G)));
 }
-inline int64_t ceil_div_frac(double num, double den) {
-  double q = num / den;
-  int64_t f = (int64_t)q;
-  return (double)f < q ? f + 1 : f;
+// ceil(a * b / den) exactly (the budgets s_avg and c_avg are rationals); an all-zero zone (den = 0) asks for one bucket
+inline int64_t ceil_ratio(int64_t a, int64_t b, int64_t den) {
+  if (den <= 0) return 1;
+  const unsigned __int128 num = (unsigned __int128)a * (unsigned __int128)b;
+  return (int64_t)((num + (unsigned __int128)(den - 1)) / (unsigned __int128)den);
 }
 template <class Load>
 int argmin_load(const Load &load) {
@@ -59,10 +60,10 @@ extern "C" int zp_partition(const int32_t *lengths, int32_t S, int32_t P, int32_
     if (split > 0) {
       int64_t total = 0;
       for (int i = 0; i < split; i++) total += lengths[order[i]];
-      const double s_avg = (double)total / N;
       for (int i = 0; i < split; i++) {
         const int32_t s = order[i];
-        const int32_t k = (int32_t)std::min<int64_t>(N, ceil_div_frac((double)lengths[s], s_avg));
+        // ceil(|s| / s_avg) with s_avg = total / N
+        const int32_t k = (int32_t)std::max<int64_t>(1, std::min<int64_t>(N, ceil_ratio(lengths[s], N, total)));  // an empty sequence still gets a bucket
         std::vector<int> idx(N);
         std::iota(idx.begin(), idx.end(), 0);
         std::stable_sort(idx.begin(), idx.end(), [&](int a, int b) { return load[a] < load[b]; });
@@ -117,13 +118,22 @@ extern "C" int zp_partition(const int32_t *lengths, int32_t S, int32_t P, int32_
       int split = 0;  // whole[0 .. split) is z1 (length >= s0), the rest z0
       while (split < (int)whole.size() && lengths[whole[split]] >= s0) split++;
       if (split > 0) {
-        double c_sum = 0;
-        for (int i = 0; i < split; i++) c_sum += (double)lengths[whole[i]] * lengths[whole[i]];
-        const double c_avg = c_sum / P;
+        // c_avg = c_sum / P, kept as an exact fraction (128 bits: squares of 31-bit lengths, summed)
+        unsigned __int128 c_sum = 0;
+        for (int i = 0; i < split; i++) c_sum += (unsigned __int128)((int64_t)lengths[whole[i]] * lengths[whole[i]]);
         int64_t next_slot = 0;
         for (int i = 0; i < split; i++) {
           const int32_t s = whole[i];
-          const int64_t G = std::min<int64_t>(P, ceil_div_frac((double)lengths[s] * lengths[s], c_avg));
+          // ceil(|s|^2 / c_avg) = ceil(|s|^2 * P / c_sum); at most P anyway, so the quotient is clamped before narrowing
+          int64_t G = P;
+          if (c_sum > 0) {
+            const unsigned __int128 num = (unsigned __int128)((int64_t)lengths[s] * lengths[s]) * (unsigned __int128)P;
+            const unsigned __int128 q = (num + c_sum - 1) / c_sum;
+            G = q < (unsigned __int128)P ? (int64_t)q : (int64_t)P;
+            if (G < 1) G = 1;  // an empty sequence still gets a bucket
+          } else {
+            G = 1;
+          }
           for (int64_t r = 0; r < G; r++) {
             const int p = (int)(next_slot++ % P);
             const int32_t t = G > 1 ? ring_share(lengths[s], G, r) : lengths[s];

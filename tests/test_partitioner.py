@@ -42,6 +42,57 @@ def test_oracle_and_library_match_hand_worked_examples(case):
         assert canon(pl) == canon(case["rows"]) and s1 == case["s1"] and s0 == case["s0"]
 
 
+# Plausible mistakes planted in a COPY of the oracle's source (on the CPU, never in the library): each one must make
+# at least one hand-worked example fail, otherwise the examples do not pin that step of Alg. 1 / Alg. 2.
+PLANTED_MISTAKES = {
+    "s_avg over every sequence instead of the inter-node zone":
+        ("z2_tokens = sum(lengths[s] for s in z2)", "z2_tokens = sum(lengths[s] for s in order)"),
+    "floor instead of ceil for the number of node buckets":
+        ("ceil_ratio(lengths[s] * N, z2_tokens)", "((lengths[s] * N) // z2_tokens)"),
+    "most loaded nodes instead of least loaded":
+        ("key=lambda n: (load[n], n))[:k]", "key=lambda n: (-load[n], n))[:k]"),
+    "fragments numbered in load order instead of node order":
+        ("enumerate(sorted(nodes))", "enumerate(nodes)"),
+    "threshold s1 not lowered to the longest remaining sequence":
+        ("s1 = max(lengths[t] for t in z01)", "s1 = min(lengths[t] for t in z01)"),
+    "c_avg over every sequence of the node instead of the intra-node zone":
+        ("z1_cost = sum(lengths[s] ** 2 for s in z1)", "z1_cost = sum(lengths[s] ** 2 for s in z01)"),
+    "floor instead of ceil for the number of fragments":
+        ("ceil_ratio(lengths[s] ** 2 * P, z1_cost)", "((lengths[s] ** 2 * P) // z1_cost)"),
+    "linear cost |s| instead of |s|^2":
+        ("ceil_ratio(lengths[s] ** 2 * P, z1_cost)", "ceil_ratio(lengths[s] * P, sum(lengths[t] for t in z1))"),
+    "round-robin restarts at device 0 for every intra-node sequence":
+        ("            for s in z1:\n", "            for s in z1:\n                nxt = 0\n"),
+    "threshold s0 not lowered to the longest remaining sequence":
+        ("s0 = max(lengths[t] for t in z0)", "s0 = min(lengths[t] for t in z0)"),
+    "ring rank holds two neighbouring chunks instead of chunks r and 2G-1-r":
+        ("return (b(r + 1) - b(r)) + (b(2 * G - r) - b(2 * G - 1 - r))", "return b(2 * r + 2) - b(2 * r)"),
+    "local sequences to the most loaded device":
+        ("idx = min(range(P), key=lambda p: (load[p], p))", "idx = max(range(P), key=lambda p: (load[p], -p))"),
+    "local sequences to the most loaded node":
+        ("idx = min(range(N), key=lambda n: (load[n], n))", "idx = max(range(N), key=lambda n: (load[n], -n))"),
+}
+
+
+@pytest.mark.parametrize("what", sorted(PLANTED_MISTAKES))
+def test_hand_worked_examples_catch_planted_mistakes(what):
+    old, new = PLANTED_MISTAKES[what]
+    src = open(opt.__file__).read()
+    assert src.count(old) == 1, f"the oracle no longer contains the line this mistake is planted in: {old!r}"
+    ns = {"__name__": "planted"}
+    exec(compile(src.replace(old, new), "planted_" + os.path.basename(opt.__file__), "exec"), ns)
+    caught = []
+    for case in golden_cases():
+        try:
+            pl, s1, s0 = ns["partition"](case["lengths"], case["P"], case["N"], case["L"])
+            ok = canon(pl) == canon(case["rows"]) and s1 == case["s1"] and s0 == case["s0"]
+        except Exception:
+            ok = False
+        if not ok:
+            caught.append(case["name"])
+    assert caught, f"no hand-worked example notices: {what}"
+
+
 def check_properties(lengths, P, N, L, pl, s1, s0):
     by_seq = collections.defaultdict(list)
     for p in pl:
@@ -98,6 +149,13 @@ def test_degenerate_cases():
     big = [p for p in pl if p["seq"] == 0]
     assert big[0]["zone"] == 2 and big[0]["ring"] == 8 and len(big) == 8 and all(p["tokens"] == 8000 for p in big)
     assert canon(B.partition(lengths, 4, 2, 8000)[0]) == canon(pl)
+    # empty sequences behind sequences that already overfill a node or a device: the thresholds fall to 0, the empty
+    # sequences join a ring zone (length 0 against a non-zero budget, or a zero budget) and must still be placed
+    for lengths, P, L in (([10, 10, 0, 0], 2, 8), ([0, 0, 0], 2, 4), ([9, 0], 1, 4)):
+        pl, s1, s0 = opt.partition(lengths, P, 1, L)
+        assert sorted({p["seq"] for p in pl}) == list(range(len(lengths))) and sum(p["tokens"] for p in pl) == sum(lengths)
+        pl2, s1b, s0b = B.partition(lengths, P, 1, L)
+        assert canon(pl2) == canon(pl) and (s1b, s0b) == (s1, s0)
     # empty batch
     assert opt.partition([], 2, 2, 10)[0] == [] and B.partition([], 2, 2, 10)[0] == []
 
