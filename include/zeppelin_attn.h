@@ -190,6 +190,31 @@ typedef struct {
 int zp_node_segments(const int32_t *lengths, int32_t S, const zp_placement *placements, int32_t n_placements, int32_t P,
                      int32_t N, zp_segment *out, int32_t max_out, int32_t *n_out, int32_t *tokens_per_rank);
 
+/* Host helper: the runs of ONE sequence that lies contiguously at packed token tok0 and is cut into C equal-length
+ * chunks (chunk c = positions [floor(cL/C), floor((c+1)L/C)), Sec. 3.2): out[c] = {seq, c, C, pos0, len, tok0 + pos0,
+ * node 0, device 0}, the same records zp_node_segments writes for a ring sequence spread over devices. C >= 1,
+ * max_out >= C. Returns C, or a negative error code. */
+int zp_chunk_segments(int32_t seq, int32_t tok0, int32_t L, int32_t C, zp_segment *out, int32_t max_out);
+
+/* Host helper: the chunk pairs of one round of the ring sequences among `segs` (records with n_chunks > 1, and, if
+ * include_whole is non-zero, also whole sequences as "rings" of one chunk whose single pair (0, 0) is in round 0; a
+ * sequence must be present with every chunk 0 .. n_chunks-1 exactly once, ZP_EINVAL otherwise). Sec. 3.2: a ring of G
+ * devices over 2G chunks computes, over its G rounds, every causal pair (qc, kc), kc <= qc, once. On one GPU a call of
+ * chunk_attn_update / chunk_attn_partial_bwd may hold a query run and a key run only once, so the same pairs are
+ * grouped by their chunk distance: round t = the pairs (qc, qc - t), qc = t .. C-1, of every ring sequence (sequences
+ * in ascending id, qc ascending); rounds 0 .. max C - 1 together are exactly the ring's pairs. Each pair takes
+ * q_tok0/q_len/q_pos0 from the run of chunk qc and k_tok0/k_len/k_pos0 from the run of chunk qc - t; out_row0 = 0.
+ * Writes up to max_pairs pairs, the count to *n_pairs and (optional) the number of rounds to *n_rounds.
+ * Returns ZP_EWORKSPACE if max_pairs was too small (*n_pairs = needed). */
+int zp_ring_round_pairs(const zp_segment *segs, int32_t n_segs, int32_t round, int32_t include_whole, zp_pair *pairs,
+                        int32_t max_pairs, int32_t *n_pairs, int32_t *n_rounds);
+
+/* Host helper: where every token of the attention layout sits in the batch as drawn (sequence after sequence in
+ * `lengths` order): orig[run.tok0 + i] = (first drawn token of run.seq) + run.pos0 + i. n_tok must equal the tokens
+ * the runs cover, and the runs must tile [0, n_tok) (ZP_EINVAL otherwise). */
+int zp_segment_positions(const int32_t *lengths, int32_t S, const zp_segment *segs, int32_t n_segs, int64_t *orig,
+                         int64_t n_tok);
+
 /* Host helper: transfer plan of the remapping layer (Sec. 3.4, Eq. 2). A[d]: tokens per rank in the attention layout;
  * rank r sits in node r / P. The balanced target is B_i = floor(T/d) + (i < T mod d). Writes M[d*d] (row-major,
  * M[i*d+j] = tokens rank i sends to rank j) with row sums max(A-B,0), column sums max(B-A,0), minimising

@@ -36,6 +36,10 @@ class ZpPlacement(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("seq", "zone", "ring", "rank", "node", "device", "tokens")]
 
 
+class ZpSegment(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("seq", "chunk", "n_chunks", "pos0", "len", "tok0", "node", "device")]
+
+
 class ZpError(RuntimeError):
     def __init__(self, code: int, text: str):
         super().__init__(f"zeppelin_attn error {code}: {text}")
@@ -88,6 +92,16 @@ def lib() -> ctypes.CDLL:
     L.zp_partition.restype = ctypes.c_int
     L.zp_partition.argtypes = [vp, i32, i32, i32, i32, ctypes.POINTER(ZpPlacement), i32, ctypes.POINTER(i32),
                                ctypes.POINTER(i32), vp]
+    L.zp_node_segments.restype = ctypes.c_int
+    L.zp_node_segments.argtypes = [vp, i32, ctypes.POINTER(ZpPlacement), i32, i32, i32, ctypes.POINTER(ZpSegment), i32,
+                                   ctypes.POINTER(i32), vp]
+    L.zp_chunk_segments.restype = ctypes.c_int
+    L.zp_chunk_segments.argtypes = [i32, i32, i32, i32, ctypes.POINTER(ZpSegment), i32]
+    L.zp_ring_round_pairs.restype = ctypes.c_int
+    L.zp_ring_round_pairs.argtypes = [ctypes.POINTER(ZpSegment), i32, i32, i32, ctypes.POINTER(ZpPair), i32,
+                                      ctypes.POINTER(i32), ctypes.POINTER(i32)]
+    L.zp_segment_positions.restype = ctypes.c_int
+    L.zp_segment_positions.argtypes = [vp, i32, ctypes.POINTER(ZpSegment), i32, vp, i64]
     L.zp_profile_enable.restype = ctypes.c_int
     L.zp_profile_enable.argtypes = [ctypes.c_int]
     L.zp_profile_count.restype = ctypes.c_int
@@ -295,15 +309,54 @@ def mfma_probe(iters: int, random_operands: bool, out=None, stream=None):
     return out
 
 
-def ring_rounds(pairs, C: int):
-    """Groups the C(C+1)/2 causal pairs of zp_chunk_pairs (Q chunk major) into C rounds: round t = pairs (qc, qc - t)."""
-    by = {}
-    n = 0
-    for qc in range(C):
-        for kc in range(qc + 1):
-            by[(qc, kc)] = pairs[n]
-            n += 1
-    return [[by[(qc, qc - t)] for qc in range(t, C)] for t in range(C)]
+def _segments_array(segs):
+    if isinstance(segs, tuple) and len(segs) == 2 and isinstance(segs[0], ctypes.Array):
+        return segs
+    arr = (ZpSegment * max(len(segs), 1))()
+    for i, sg in enumerate(segs):
+        for f, _ in ZpSegment._fields_:
+            setattr(arr[i], f, int(sg[f]))
+    return arr, len(segs)
+
+
+def chunk_segments(tok0: int, L: int, C: int, seq: int = 0):
+    """Host helper: the runs of one contiguous sequence cut into C equal-length chunks -> (ctypes array, C)."""
+    out = (ZpSegment * C)()
+    n = lib().zp_chunk_segments(int(seq), int(tok0), int(L), int(C), out, C)
+    if n < 0:
+        _check(n)
+    return out, n
+
+
+def ring_round_pairs(segs, t: int, include_whole: bool = False):
+    """Host helper: the chunk pairs (qc, qc - t) of every ring sequence among the runs -> ((pairs array, n), rounds).
+    include_whole: whole sequences count as rings of one chunk."""
+    arr, n_segs = _segments_array(segs)
+    n = ctypes.c_int32(0)
+    rounds = ctypes.c_int32(0)
+    rc = lib().zp_ring_round_pairs(arr, n_segs, int(t), int(include_whole), None, 0, ctypes.byref(n), ctypes.byref(rounds))
+    if rc not in (0, -3):
+        _check(rc)
+    pairs = (ZpPair * max(n.value, 1))()
+    _check(lib().zp_ring_round_pairs(arr, n_segs, int(t), int(include_whole), pairs, n.value, ctypes.byref(n),
+                                     ctypes.byref(rounds)))
+    return (pairs, n.value), rounds.value
+
+
+def ring_rounds(tok0: int, L: int, C: int):
+    """All C rounds of one contiguous sequence cut into C chunks: [(pairs array, n)] with round t = pairs (qc, qc - t)."""
+    segs = chunk_segments(tok0, L, C)
+    return [ring_round_pairs(segs, t, include_whole=True)[0] for t in range(C)]
+
+
+def segment_positions(lengths, segs, n_tok: int):
+    """Host helper: attention-layout token -> token of the batch as drawn (int64 array of n_tok entries)."""
+    lens = np.ascontiguousarray(lengths, dtype=np.int32)
+    arr, n_segs = _segments_array(segs)
+    orig = np.zeros(int(n_tok), np.int64)
+    _check(lib().zp_segment_positions(lens.ctypes.data_as(ctypes.c_void_p), len(lens), arr, n_segs,
+                                      orig.ctypes.data_as(ctypes.c_void_p), int(n_tok)))
+    return orig
 
 
 def lse_merge(o_part, lse_part, merges, o, lse, ws=None, stream=None):
@@ -383,10 +436,6 @@ def remap_indices(A, M):
     return idx
 
 
-class ZpSegment(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int32) for n in ("seq", "chunk", "n_chunks", "pos0", "len", "tok0", "node", "device")]
-
-
 def node_segments(lengths, placements, P: int, N: int):
     """Host helper: attention layout of a placement list -> (runs as dicts, tokens per device)."""
     lens = np.ascontiguousarray(lengths, dtype=np.int32)
@@ -398,7 +447,6 @@ def node_segments(lengths, placements, P: int, N: int):
     out = (ZpSegment * cap)()
     n = ctypes.c_int32(0)
     A = np.zeros(P * N, np.int32)
-    lib().zp_node_segments.restype = ctypes.c_int
     _check(lib().zp_node_segments(lens.ctypes.data_as(ctypes.c_void_p), len(lens), arr, len(placements), int(P), int(N),
                                   out, cap, ctypes.byref(n), A.ctypes.data_as(ctypes.c_void_p)))
     segs = [{f: getattr(out[i], f) for f, _ in ZpSegment._fields_} for i in range(n.value)]

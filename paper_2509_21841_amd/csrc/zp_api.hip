@@ -12,6 +12,7 @@
 
 #include "../../include/zeppelin_attn.h"
 #include "zp_common.h"
+#include "zp_pool.h"
 
 extern "C" {
 int zp_launch_attn_fwd(const zp_attn_params *p, int d, int partial, int block_rows, hipStream_t stream);
@@ -60,57 +61,32 @@ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // ---- pinned staging pool -------------------------------------------------------------------------
 // Descriptor tables are built in pinned host memory and copied with hipMemcpyAsync; a slot is reused only
-// after the event recorded behind its copy has completed, so the host never overwrites bytes in flight.
-struct Slot {
-  void *host = nullptr;
-  size_t cap = 0;
-  hipEvent_t ev = nullptr;
-  bool in_flight = false;
+// after the event recorded behind its copy has completed, so the host never overwrites bytes in flight
+// (zp_pool.h holds the slot state machine; this is its HIP backend).
+struct HipPoolBackend {
+  typedef hipEvent_t event_t;
+  typedef hipStream_t stream_t;
+  static int alloc(void **p, size_t bytes) { return (int)hipHostMalloc(p, bytes, hipHostMallocDefault); }
+  static void release(void *p) { (void)hipHostFree(p); }
+  static int event_create(event_t *e) { return (int)hipEventCreateWithFlags(e, hipEventDisableTiming); }
+  static int event_record(event_t e, stream_t s) { return (int)hipEventRecord(e, s); }
+  static bool event_done(event_t e) { return hipEventQuery(e) == hipSuccess; }
 };
-std::mutex g_pool_mu;
-std::vector<Slot> g_pool;
+zp_staging_pool<HipPoolBackend> g_pool;
 
-int pool_acquire(size_t bytes, int *slot_out) {
-  std::lock_guard<std::mutex> lk(g_pool_mu);
-  for (size_t i = 0; i < g_pool.size(); i++) {
-    Slot &s = g_pool[i];
-    if (s.cap < bytes) continue;
-    if (s.in_flight) {
-      if (hipEventQuery(s.ev) != hipSuccess) continue;
-      s.in_flight = false;
-    }
-    s.in_flight = true;  // reserved by this call
-    *slot_out = (int)i;
-    return ZP_OK;
-  }
-  Slot s;
-  s.cap = std::max<size_t>(align256(bytes), 1 << 16);
-  ZP_HIP(hipHostMalloc(&s.host, s.cap, hipHostMallocDefault), "hipHostMalloc");
-  ZP_HIP(hipEventCreateWithFlags(&s.ev, hipEventDisableTiming), "hipEventCreate");
-  s.in_flight = true;
-  g_pool.push_back(s);
-  *slot_out = (int)g_pool.size() - 1;
-  return ZP_OK;
+int pool_acquire(size_t bytes, int *slot_out, void **host_out) {
+  const int e = g_pool.acquire(bytes, slot_out, host_out);
+  return e ? hip_fail((hipError_t)e, "staging buffer") : ZP_OK;
 }
-
 // Copy `bytes` from the slot to device memory on `stream` and mark the slot busy until the copy is done.
-int pool_upload(int slot, void *dev, size_t bytes, hipStream_t stream) {
-  Slot s;
-  {
-    std::lock_guard<std::mutex> lk(g_pool_mu);
-    s = g_pool[slot];
+int pool_upload(int slot, const void *host, void *dev, size_t bytes, hipStream_t stream) {
+  hipError_t e = hipMemcpyAsync(dev, host, bytes, hipMemcpyHostToDevice, stream);
+  if (e != hipSuccess) {
+    g_pool.abandon(slot);
+    return hip_fail(e, "hipMemcpyAsync");
   }
-  ZP_HIP(hipMemcpyAsync(dev, s.host, bytes, hipMemcpyHostToDevice, stream), "hipMemcpyAsync");
-  ZP_HIP(hipEventRecord(s.ev, stream), "hipEventRecord");
-  return ZP_OK;
-}
-void *pool_ptr(int slot) {
-  std::lock_guard<std::mutex> lk(g_pool_mu);
-  return g_pool[slot].host;
-}
-void pool_release_unused(int slot) {
-  std::lock_guard<std::mutex> lk(g_pool_mu);
-  g_pool[slot].in_flight = false;
+  const int r = g_pool.submitted(slot, stream);
+  return r ? hip_fail((hipError_t)r, "hipEventRecord") : ZP_OK;
 }
 
 // ---- per-kernel timing (measurement aid) -----------------------------------------------------------
@@ -205,13 +181,12 @@ int upload_tiles(const std::vector<CostTile> &tiles, void *ws, hipStream_t strea
   if (tiles.empty()) return ZP_OK;
   const size_t bytes = tiles.size() * sizeof(zp_tile);
   int slot;
-  int rc = pool_acquire(bytes, &slot);
+  void *host;
+  int rc = pool_acquire(bytes, &slot, &host);
   if (rc) return rc;
-  zp_tile *h = (zp_tile *)pool_ptr(slot);
+  zp_tile *h = (zp_tile *)host;
   for (size_t i = 0; i < tiles.size(); i++) h[i] = tiles[i].t;
-  rc = pool_upload(slot, ws, bytes, stream);
-  if (rc) pool_release_unused(slot);
-  return rc;
+  return pool_upload(slot, host, ws, bytes, stream);
 }
 
 }  // namespace
@@ -468,8 +443,9 @@ int lse_merge(const float *o_part, const float *lse_part, int64_t part_rows, con
   if ((rc = check_ws(ws, ws_bytes, desc_bytes + align256(item_bytes)))) return rc;
   if (n_items == 0) return ZP_OK;
   int slot;
-  if ((rc = pool_acquire(desc_bytes + item_bytes, &slot))) return rc;
-  char *h = (char *)pool_ptr(slot);
+  void *host;
+  if ((rc = pool_acquire(desc_bytes + item_bytes, &slot, &host))) return rc;
+  char *h = (char *)host;
   std::memcpy(h, merges, (size_t)n_merges * sizeof(zp_merge));
   int32_t *items = (int32_t *)(h + desc_bytes);
   size_t n = 0;
@@ -479,8 +455,7 @@ int lse_merge(const float *o_part, const float *lse_part, int64_t part_rows, con
       items[2 * n + 1] = r0;
       n++;
     }
-  rc = pool_upload(slot, ws, desc_bytes + item_bytes, (hipStream_t)stream);
-  if (rc) { pool_release_unused(slot); return rc; }
+  if ((rc = pool_upload(slot, host, ws, desc_bytes + item_bytes, (hipStream_t)stream))) return rc;
   int max_parts = 1;
   for (int i = 0; i < n_merges; i++) max_parts = std::max(max_parts, (int)merges[i].n_parts);
   hipError_t e = (hipError_t)zp_launch_lse_merge(o_part, lse_part, part_rows, ws, (char *)ws + desc_bytes, (int)n_items,

@@ -3,6 +3,7 @@
 // zone), i.e. what the attention engine's work list on each device is made of. Pure integer host code.
 #include <algorithm>
 #include <cstdint>
+#include <map>
 #include <numeric>
 #include <vector>
 
@@ -204,4 +205,79 @@ extern "C" int zp_node_segments(const int32_t *lengths, int32_t S, const zp_plac
     }
   *n_out = n;
   return n > max_out ? ZP_EWORKSPACE : ZP_OK;
+}
+
+// The runs of one contiguous sequence cut into C equal-length chunks (Sec. 3.2).
+extern "C" int zp_chunk_segments(int32_t seq, int32_t tok0, int32_t L, int32_t C, zp_segment *out, int32_t max_out) {
+  if (!out || seq < 0 || tok0 < 0 || L < 0 || C < 1 || max_out < C || (int64_t)tok0 + L > INT32_MAX) return ZP_EINVAL;
+  for (int32_t c = 0; c < C; c++) {
+    const int64_t p0 = (int64_t)c * L / C, p1 = (int64_t)(c + 1) * L / C;
+    out[c] = zp_segment{seq, c, C, (int32_t)p0, (int32_t)(p1 - p0), (int32_t)(tok0 + p0), 0, 0};
+  }
+  return C;
+}
+
+// Round t of the ring sequences among the runs: the pairs (qc, qc - t) (Sec. 3.2; grouping by chunk distance keeps
+// every query run and every key run single inside a call).
+extern "C" int zp_ring_round_pairs(const zp_segment *segs, int32_t n_segs, int32_t round, int32_t include_whole,
+                                   zp_pair *pairs, int32_t max_pairs, int32_t *n_pairs, int32_t *n_rounds) {
+  if (!segs || n_segs < 0 || round < 0 || !n_pairs || max_pairs < 0 || (max_pairs > 0 && !pairs)) return ZP_EINVAL;
+  std::map<int32_t, std::vector<int32_t>> chunks;  // ring sequence -> index of the run of every chunk
+  for (int32_t i = 0; i < n_segs; i++) {
+    const zp_segment &sg = segs[i];
+    if (sg.n_chunks < 1 || sg.chunk < 0 || sg.chunk >= sg.n_chunks || sg.len < 0 || sg.tok0 < 0 || sg.pos0 < 0 || sg.seq < 0)
+      return ZP_EINVAL;
+    if (sg.n_chunks == 1 && !include_whole) continue;
+    auto &v = chunks[sg.seq];
+    if (v.empty()) v.assign(sg.n_chunks, -1);
+    if ((int32_t)v.size() != sg.n_chunks || v[sg.chunk] != -1) return ZP_EINVAL;
+    v[sg.chunk] = i;
+  }
+  int32_t n = 0, rounds = 0;
+  for (const auto &kv : chunks) {
+    const std::vector<int32_t> &v = kv.second;
+    const int32_t C = (int32_t)v.size();
+    for (int32_t c = 0; c < C; c++)
+      if (v[c] < 0) return ZP_EINVAL;
+    rounds = std::max(rounds, C);
+    for (int32_t qc = round; qc < C; qc++) {
+      const zp_segment &sq = segs[v[qc]], &sk = segs[v[qc - round]];
+      if (n < max_pairs) pairs[n] = zp_pair{sq.tok0, sq.len, sk.tok0, sk.len, sq.pos0, sk.pos0, 0};
+      n++;
+    }
+  }
+  *n_pairs = n;
+  if (n_rounds) *n_rounds = rounds;
+  return n > max_pairs ? ZP_EWORKSPACE : ZP_OK;
+}
+
+// Attention-layout token -> token of the batch as drawn.
+extern "C" int zp_segment_positions(const int32_t *lengths, int32_t S, const zp_segment *segs, int32_t n_segs,
+                                    int64_t *orig, int64_t n_tok) {
+  if (!lengths || !segs || S < 0 || n_segs < 0 || n_tok < 0 || (n_tok > 0 && !orig)) return ZP_EINVAL;
+  std::vector<int64_t> first(S + 1, 0);
+  for (int s = 0; s < S; s++) {
+    if (lengths[s] < 0) return ZP_EINVAL;
+    first[s + 1] = first[s] + lengths[s];
+  }
+  std::vector<std::pair<int64_t, int64_t>> cover;
+  for (int32_t i = 0; i < n_segs; i++) {
+    const zp_segment &sg = segs[i];
+    if (sg.seq < 0 || sg.seq >= S || sg.len < 0 || sg.pos0 < 0 || sg.tok0 < 0 || (int64_t)sg.pos0 + sg.len > lengths[sg.seq] ||
+        (int64_t)sg.tok0 + sg.len > n_tok)
+      return ZP_EINVAL;
+    if (sg.len > 0) cover.push_back({sg.tok0, (int64_t)sg.tok0 + sg.len});
+  }
+  std::sort(cover.begin(), cover.end());
+  int64_t at = 0;
+  for (const auto &c : cover) {
+    if (c.first != at) return ZP_EINVAL;
+    at = c.second;
+  }
+  if (at != n_tok) return ZP_EINVAL;
+  for (int32_t i = 0; i < n_segs; i++) {
+    const zp_segment &sg = segs[i];
+    for (int32_t j = 0; j < sg.len; j++) orig[(int64_t)sg.tok0 + j] = first[sg.seq] + sg.pos0 + j;
+  }
+  return ZP_OK;
 }

@@ -29,30 +29,18 @@ class NodePlan:
         self.cu[1:] = np.cumsum([s["len"] for s in self.segments])
         self.skip = np.asarray([1 if s["n_chunks"] > 1 else 0 for s in self.segments], np.uint8)
         # attention-layout position -> position in the batch as drawn (sequence after sequence)
-        orig_cu = np.concatenate([[0], np.cumsum(self.lengths)])
-        self.orig = np.concatenate([orig_cu[s["seq"]] + s["pos0"] + np.arange(s["len"]) for s in self.segments]
-                                   or [np.zeros(0, np.int64)]).astype(np.int64)
-        by_seq = {}
-        for s in self.segments:
-            if s["n_chunks"] > 1:
-                by_seq.setdefault(s["seq"], {})[s["chunk"]] = s
+        self.orig = B.segment_positions(self.lengths, self.segments, self.T)
         self.ring_segments = [s for s in self.segments if s["n_chunks"] > 1]
-        # ring rounds: round t holds the pairs (qc, qc - t) of every ring sequence, so no query run and no key run
-        # appears twice in a call
-        self.max_chunks = max([s["n_chunks"] for s in self.ring_segments], default=0)
-        self.rounds = []
-        for t in range(self.max_chunks):
-            rnd = []
-            for seq, ch in sorted(by_seq.items()):
-                C = len(ch)
-                for qc in range(t, C):
-                    sq, sk = ch[qc], ch[qc - t]
-                    rnd.append(dict(q_tok0=sq["tok0"], q_len=sq["len"], k_tok0=sk["tok0"], k_len=sk["len"],
-                                    q_pos0=sq["pos0"], k_pos0=sk["pos0"], out_row0=0))
-            arr, n = B._pairs_array(rnd)
-            self.rounds.append((arr, n))
-        self.ring_pairs = sum(L_ * (L_ + 1) // 2 for seq, L_ in enumerate(self.lengths) if seq in by_seq)
-        self.local_pairs = sum(L_ * (L_ + 1) // 2 for seq, L_ in enumerate(self.lengths) if seq not in by_seq)
+        ring_seqs = {s["seq"] for s in self.ring_segments}
+        # ring rounds (zp_ring_round_pairs): round t holds the pairs (qc, qc - t) of every ring sequence, so no query
+        # run and no key run appears twice in a call
+        self.max_chunks, self.rounds = 0, []
+        if self.ring_segments:
+            segs = B._segments_array(self.segments)
+            first, self.max_chunks = B.ring_round_pairs(segs, 0)
+            self.rounds = [first] + [B.ring_round_pairs(segs, t)[0] for t in range(1, self.max_chunks)]
+        self.ring_pairs = sum(L_ * (L_ + 1) // 2 for seq, L_ in enumerate(self.lengths) if seq in ring_seqs)
+        self.local_pairs = sum(L_ * (L_ + 1) // 2 for seq, L_ in enumerate(self.lengths) if seq not in ring_seqs)
 
 
 class NodeJob:

@@ -172,7 +172,7 @@ def test_every_entry_point_is_deterministic(lengths, Hq, Hkv, d):
         o_run = torch.zeros((T, Hq, d), dtype=torch.float32, device=DEV)
         lse_run = torch.full((Hq, T), float("-inf"), dtype=torch.float32, device=DEV)
         acc = [torch.zeros(x.shape, dtype=torch.float32, device=DEV) for x in (q, k, v)]
-        for rnd in B.ring_rounds(pairs, 4):
+        for rnd in B.ring_rounds(0, L, 4):
             B.chunk_attn_update(q, k, v, rnd, o_run, lse_run)
             B.chunk_attn_partial_bwd(do, q, k, v, o, lse, rnd, *acc)
         torch.cuda.synchronize()
@@ -227,7 +227,7 @@ def test_rounds_merged_in_place_equal_whole(L, C, Hq, Hkv, d):
     lse_run = torch.full((Hq, T), float("-inf"), dtype=torch.float32, device=DEV)
     ro = np.zeros((T, Hq, d)); rl = np.full((Hq, T), -np.inf)
     qw, kw, vw = widen(q), widen(k), widen(v)
-    for rnd, ornd in zip(B.ring_rounds(pairs, C), oracle.ring_rounds(C)):
+    for rnd, ornd in zip(B.ring_rounds(t0, L, C), oracle.ring_rounds(C)):
         B.chunk_attn_update(q, k, v, rnd, o_run, lse_run)
         # oracle: this round's partials, then merged with the running rows as one more part
         plist = []
@@ -312,7 +312,7 @@ def run_chunked_bwd(lengths, which, C, Hq, Hkv, d, seed, scale=0.0):
     t0, L = int(cu[which]), lengths[which]
     pairs, _, _ = B.chunk_pairs(t0, L, C)
     acc = [torch.zeros(x.shape, dtype=torch.float32, device=DEV) for x in (q, k, v)]
-    for rnd in B.ring_rounds(pairs, C):
+    for rnd in B.ring_rounds(t0, L, C):
         B.chunk_attn_partial_bwd(do, q, k, v, o, lse, rnd, *acc, scale=scale)
     torch.cuda.synchronize()
     rdq, rdk, rdv = oracle.varlen_attn_bwd(widen(do), widen(q), widen(k), widen(v), cu, scale=scale or None)
@@ -338,7 +338,7 @@ def test_chunked_backward_custom_scale_and_single_round_against_oracle():
     (q, k, v, do), cu = make(lengths, 4, 2, 128, 43, with_dout=True)
     o, lse = B.varlen_attn_fwd(q, k, v, cu)
     pairs, _, _ = B.chunk_pairs(0, 900, 4)
-    rnd = B.ring_rounds(pairs, 4)[2]
+    rnd = B.ring_rounds(0, 900, 4)[2]
     acc = [torch.zeros(x.shape, dtype=torch.float32, device=DEV) for x in (q, k, v)]
     B.chunk_attn_partial_bwd(do, q, k, v, o, lse, rnd, *acc)
     B.chunk_attn_partial_bwd(do, q, k, v, o, lse, rnd, *acc)     # a second call adds the same again

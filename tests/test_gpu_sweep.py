@@ -53,7 +53,7 @@ def test_random_configurations(seed):
         o_run = torch.zeros((T, Hq, d), dtype=torch.float32, device=DEV)
         lse_run = torch.full((Hq, T), float("-inf"), dtype=torch.float32, device=DEV)
         acc = [torch.zeros(x.shape, dtype=torch.float32, device=DEV) for x in (q, k, v)]
-        for rnd in B.ring_rounds(pairs, C):
+        for rnd in B.ring_rounds(t0, L, C):
             B.chunk_attn_update(q, k, v, rnd, o_run, lse_run, scale=scale)
             B.chunk_attn_partial_bwd(do, q, k, v, o, lse, rnd, *acc, scale=scale)
         torch.cuda.synchronize()

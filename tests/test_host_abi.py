@@ -143,3 +143,63 @@ def test_table2_length_mixes():
         hist = np.histogram(big, bins=synth.TABLE2_EDGES)[0] / len(big)
         want = np.asarray(probs) / sum(probs)
         assert np.abs(hist - want).max() < 0.02, (name, hist, want)
+
+
+def _pair_tuple(p):
+    return tuple(getattr(p, f) if not isinstance(p, dict) else p[f] for f in ("q_tok0", "q_len", "k_tok0", "k_len", "q_pos0", "k_pos0"))
+
+
+@pytest.mark.parametrize("tok0,L,C", [(0, 1000, 4), (37, 777, 3), (5, 130, 8), (0, 5, 8), (11, 2100, 16), (3, 64, 1)])
+def test_ring_round_pairs_match_the_oracle_rounds_and_the_ring_schedule(tok0, L, C):
+    """zp_chunk_segments + zp_ring_round_pairs against the oracle: round t is the oracle's pairs (qc, qc - t) with the
+    oracle's chunk descriptors; over all rounds they are exactly what the ranks of a ring of C/2 devices compute over
+    its rounds (Sec. 3.2), each pair once."""
+    opairs, _, _ = oracle.causal_pairs(tok0, L, C)
+    by = dict(zip([(qc, kc) for qc in range(C) for kc in range(qc + 1)], opairs))
+    rounds = B.ring_rounds(tok0, L, C)
+    assert len(rounds) == C == len(oracle.ring_rounds(C))
+    seen = []
+    for (arr, n), ornd in zip(rounds, oracle.ring_rounds(C)):
+        assert [_pair_tuple(arr[i]) for i in range(n)] == [_pair_tuple(by[pr]) for pr in ornd]
+        # inside a round no query run and no key run appears twice
+        qs = [arr[i].q_tok0 for i in range(n) if arr[i].q_len]
+        ks = [arr[i].k_tok0 for i in range(n) if arr[i].k_len]
+        assert len(set(qs)) == len(qs) and len(set(ks)) == len(ks)
+        seen += ornd
+    if C % 2 == 0:
+        G = C // 2
+        ring = [pr for rank in oracle.ring_schedule(G) for rnd in rank for pr in rnd]
+        assert sorted(ring) == sorted(seen) and len(set(ring)) == len(ring)
+
+
+def test_ring_round_pairs_over_scattered_runs_and_bad_input():
+    # two ring sequences whose chunks sit in different device buffers (as zp_node_segments lays them out) + a whole one
+    segs = [dict(seq=0, chunk=0, n_chunks=4, pos0=0, len=25, tok0=0, node=0, device=0),
+            dict(seq=0, chunk=3, n_chunks=4, pos0=75, len=25, tok0=25, node=0, device=0),
+            dict(seq=2, chunk=0, n_chunks=1, pos0=0, len=9, tok0=50, node=0, device=0),
+            dict(seq=0, chunk=1, n_chunks=4, pos0=25, len=25, tok0=59, node=0, device=1),
+            dict(seq=0, chunk=2, n_chunks=4, pos0=50, len=25, tok0=84, node=0, device=1),
+            dict(seq=1, chunk=1, n_chunks=2, pos0=3, len=4, tok0=109, node=0, device=1),
+            dict(seq=1, chunk=0, n_chunks=2, pos0=0, len=3, tok0=113, node=0, device=1)]
+    at = {(s["seq"], s["chunk"]): s for s in segs}
+    for t in range(4):
+        (arr, n), rounds = B.ring_round_pairs(segs, t)
+        assert rounds == 4
+        want = [(0, qc, qc - t) for qc in range(t, 4)] + [(1, qc, qc - t) for qc in range(t, 2)]
+        got = [_pair_tuple(arr[i]) for i in range(n)]
+        assert got == [(at[(s, qc)]["tok0"], at[(s, qc)]["len"], at[(s, kc)]["tok0"], at[(s, kc)]["len"],
+                        at[(s, qc)]["pos0"], at[(s, kc)]["pos0"]) for s, qc, kc in want]
+    with pytest.raises(B.ZpError):
+        B.ring_round_pairs(segs[:4], 0)             # a ring sequence with a chunk missing
+    with pytest.raises(B.ZpError):
+        B.ring_round_pairs(segs + [segs[0]], 0)     # a chunk twice
+    # layout position -> drawn position
+    lengths = [100, 7, 9]
+    orig = B.segment_positions(lengths, segs, 116)
+    first = np.concatenate([[0], np.cumsum(lengths)])
+    want = np.zeros(116, np.int64)
+    for s in segs:
+        want[s["tok0"]:s["tok0"] + s["len"]] = first[s["seq"]] + s["pos0"] + np.arange(s["len"])
+    assert np.array_equal(orig, want) and sorted(orig.tolist()) == list(range(116))
+    with pytest.raises(B.ZpError):
+        B.segment_positions(lengths, segs[:-1], 116)    # the runs do not tile the layout
