@@ -32,6 +32,8 @@ HBM_PEAK_GBPS = 8000.0
 MEASURED_TRAFFIC_BYTES = {("longtail-128k-gqa32x8", "attn_bwd_dkdv"): (7831163 * 2.00 + 524736 * 1.00) * 1024,
                           ("longtail-128k-gqa32x8", "attn_bwd_dq"): (5537909 * 2.00 + 1149559 * 1.00) * 1024}
 
+TRAFFIC_SOURCE = "profiles/bench_longtail-128k-gqa32x8_hbm_traffic.txt"
+
 WORKLOADS = {
     # name: (T, Hq, Hkv, d, seed, length recipe, chunks for long sequences, backward?, remap?)
     "longtail-128k-gqa32x8": dict(T=131072, Hq=32, Hkv=8, d=128, seed=1003, mix="longtail", C=4, bwd=True, remap=True),
@@ -266,6 +268,68 @@ def mfma_sustained(iters: int = 60000):
     return out
 
 
+def make_job(name, dev):
+    return NodeBenchJob(name, dev) if WORKLOADS[name].get("node") else Job(name, dev)
+
+
+def measure(job, steps: int, warmup: int):
+    """`warmup` untimed steps, then exactly `steps` timed ones between two events on the launch stream with a device
+    synchronisation on both sides. Returns (ms per step, host wall seconds, per-kernel durations from the events the
+    library records around each launch on that same stream)."""
+    for _ in range(warmup):
+        job.step()
+    torch.cuda.synchronize()
+    B.profile_enable(True)
+    stream = torch.cuda.current_stream()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for _ in range(steps):
+        job.step()
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_step = ev0.elapsed_time(ev1) / steps
+    recs = B.profile_records()
+    B.profile_enable(False)
+    by = {}
+    for label, ms in recs:
+        by.setdefault(label, []).append(ms)
+    kern = {k: {"launches_per_step": len(v) // steps, "avg_ms": float(np.mean(v)), "ms_per_step": float(np.sum(v)) / steps}
+            for k, v in by.items()}
+    return ms_step, wall, kern
+
+
+def fwd_bwd_rates(job, kern):
+    fwd_ms = sum(kern[k]["ms_per_step"] for k in ("attn_fwd", "attn_fwd_partial", "lse_merge") if k in kern)
+    bwd_ms = sum(kern[k]["ms_per_step"] for k in ("attn_bwd_dq", "attn_bwd_dkdv") if k in kern)
+    return (job.flops_fwd / (fwd_ms * 1e-3) / 1e12 if fwd_ms else None,
+            job.flops_bwd / (bwd_ms * 1e-3) / 1e12 if bwd_ms else None)
+
+
+# the short-sequence configurations, reported beside the headline in the same JSON line (outside its timed region)
+SECONDARY = ("lognormal-64k-mha32", "lognormal-256k-gqa64x8")
+
+
+def secondary_workloads(dev, steps: int, warmup: int):
+    out = {}
+    for name in SECONDARY:
+        job = make_job(name, dev)
+        ms_step, _, kern = measure(job, steps, warmup)
+        value = (job.flops_fwd + job.flops_bwd) / (ms_step * 1e-3) / 1e12
+        fwd, bwd = fwd_bwd_rates(job, kern)
+        dom = max((k for k in kern if k.startswith("attn")), key=lambda k: kern[k]["ms_per_step"])
+        out[name] = {"value": value, "unit": "TFLOP/s", "ms_per_step": ms_step, "steps": steps,
+                     "frac_of_mfma_peak": value / MFMA_BF16_PEAK_TFLOPS, "fwd_tflops": fwd, "bwd_tflops": bwd,
+                     "n_sequences": len(job.lengths), "max_len": max(job.lengths),
+                     "dominant_kernel": dom, "dominant_kernel_frac_of_mfma_peak":
+                         kernel_flops(job, dom) / (kern[dom]["ms_per_step"] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+        del job
+        torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -273,6 +337,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="longtail-128k-gqa32x8", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-secondary", action="store_true", help="skip the short-sequence workloads reported beside the headline")
     a = ap.parse_args()
     if WORKLOADS[a.workload].get("rank_share") or WORKLOADS[a.workload].get("node") or not WORKLOADS[a.workload]["bwd"]:
         a.no_cpu_baseline = True   # the oracle sample is defined for the forward+backward workloads
@@ -285,36 +350,20 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     B.lib()
-    job = NodeBenchJob(a.workload, dev) if WORKLOADS[a.workload].get("node") else Job(a.workload, dev)
-    for _ in range(a.warmup):
-        job.step()
-    torch.cuda.synchronize()
-    B.profile_enable(True)
-    stream = torch.cuda.current_stream()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    ev0.record(stream)
-    for _ in range(a.steps):
-        job.step()
-    ev1.record(stream)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ms_step = ev0.elapsed_time(ev1) / a.steps
-    recs = B.profile_records()
-    B.profile_enable(False)
+    job = make_job(a.workload, dev)
+    ms_step, wall, kern = measure(job, a.steps, a.warmup)
     sustained = mfma_sustained()
 
-    by = {}
-    for label, ms in recs:
-        by.setdefault(label, []).append(ms)
-    kern = {k: {"launches_per_step": len(v) // a.steps, "avg_ms": float(np.mean(v)), "ms_per_step": float(np.sum(v)) / a.steps}
-            for k, v in by.items()}
     attn = {k: v for k, v in kern.items() if k.startswith("attn")}
     dom = max(attn, key=lambda k: attn[k]["ms_per_step"])
     ach = kernel_flops(job, dom) / (kern[dom]["ms_per_step"] * 1e-3) / 1e12
     roofline = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": MEASURED_TRAFFIC_BYTES.get((a.workload, dom)),
+                # not measured by this run: a stored figure from the rocprofv3 --pmc runs summarised in the file named
+                # here; the FETCH_SIZE scale factor read 2.00 on 16 KiB rows but 1.00 on 2 KiB rows, so the fetch part
+                # is known to within a factor of two
+                "traffic_source": TRAFFIC_SOURCE if (a.workload, dom) in MEASURED_TRAFFIC_BYTES else None,
+                "traffic_note": "stored profile constant, not measured in this run; FETCH_SIZE scale factor uncertain (1.0-2.0)",
                 "mfma_sustained_tflops": sustained,
                 "frac_of_sustained_random_operands": ach / sustained["random_operands"]}
     total_flops = job.flops_fwd + job.flops_bwd
@@ -337,10 +386,7 @@ def main():
         "kernels": kern,
         "host_wall_ms_per_step": wall * 1e3 / a.steps,
     }
-    fwd_ms = sum(kern[k]["ms_per_step"] for k in ("attn_fwd", "attn_fwd_partial", "lse_merge") if k in kern)
-    bwd_ms = sum(kern[k]["ms_per_step"] for k in ("attn_bwd_dq", "attn_bwd_dkdv") if k in kern)
-    out["fwd_tflops"] = job.flops_fwd / (fwd_ms * 1e-3) / 1e12 if fwd_ms else None
-    out["bwd_tflops"] = job.flops_bwd / (bwd_ms * 1e-3) / 1e12 if bwd_ms else None
+    out["fwd_tflops"], out["bwd_tflops"] = fwd_bwd_rates(job, kern)
     if "remap" in kern:
         gbps = job.remap_bytes / (kern["remap"]["ms_per_step"] * 1e-3) / 1e9
         out["remap"] = {"GBps": gbps, "frac_of_hbm_peak": gbps / HBM_PEAK_GBPS, "bytes_per_step": job.remap_bytes}
@@ -349,6 +395,10 @@ def main():
         out["lse_merge"] = {"GBps": gbps, "frac_of_hbm_peak": gbps / HBM_PEAK_GBPS, "bytes_per_step": job.merge_bytes}
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(job)
+    if a.workload == "longtail-128k-gqa32x8" and not a.no_secondary:
+        del job
+        torch.cuda.empty_cache()
+        out["secondary"] = secondary_workloads(dev, max(2, min(a.steps, 5)), max(1, min(a.warmup, 2)))
     print(json.dumps(out))
 
 

@@ -21,6 +21,7 @@
  *    sequence at the same or an earlier position (Sec. 2.1: lower-triangular mask; Sec. 2.3 / 3.2:
  *    no cross-sequence attention, local sequences use a variable-length kernel).
  *  - Supported: d in {64, 128}; Hq % Hkv == 0; bfloat16 inputs, float32 accumulation.
+ * Measurement aids (per-kernel timing, a device probe) are declared in zeppelin_attn_bench.h, not here.
  */
 #ifndef ZEPPELIN_ATTN_H
 #define ZEPPELIN_ATTN_H
@@ -232,24 +233,6 @@ int zp_remap_plan(const int32_t *A, int32_t d, int32_t P, int32_t b_intra, int32
  * takes the attention layout to the balanced one and mode 1 takes it back. Returns ZP_EINVAL if M does not move
  * exactly every surplus and deficit or n_idx != sum A. */
 int zp_remap_indices(const int32_t *A, const int32_t *M, int32_t d, int32_t *idx, int64_t n_idx);
-
-/* Measurement aid: enqueues a register-only loop of bf16 MFMAs (256 workgroups x 4 waves, iters * 32 instructions of
- * 32x32x16 per wave = 256 * 4 * iters * 32 * 32768 flop in total) with all-zero (random_operands = 0) or random
- * operand values, so a caller that times the launch learns the MFMA rate the chip sustains on such data: the clock
- * held under random operands is lower than under zeros. out: device, ZP_MFMA_PROBE_OUT_BYTES bytes, overwritten.
- * iters in [1, 2^22]. Returns ZP_EINVAL on a null or misaligned pointer or iters out of range. */
-#define ZP_MFMA_PROBE_OUT_BYTES 262144
-#define ZP_MFMA_PROBE_FLOP_PER_ITER 1073741824.0 /* 256 * 4 * 32 * 32768 */
-int zp_mfma_probe(float *out, int32_t iters, int32_t random_operands, void *stream);
-
-/* Measurement aid: per-kernel durations from hipEvents recorded on the launch stream.
- * zp_profile_enable(1) clears the records and starts recording every kernel the library launches (one
- * record per launch, in launch order); zp_profile_enable(0) stops and clears. zp_profile_get() waits for
- * record i to finish and returns its kernel label (truncated to name_cap-1 chars) and duration in ms.
- * Event creation is a host-side allocation: keep it off in production loops. */
-int zp_profile_enable(int on);
-int zp_profile_count(void);
-int zp_profile_get(int i, char *name, int name_cap, float *ms);
 
 const char *zp_strerror(int code);
 

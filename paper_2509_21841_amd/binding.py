@@ -83,8 +83,6 @@ def lib() -> ctypes.CDLL:
     L.zp_remap_plan.argtypes = [vp, i32, i32, i32, i32, vp, ctypes.POINTER(i64)]
     L.zp_remap_indices.restype = ctypes.c_int
     L.zp_remap_indices.argtypes = [vp, vp, i32, vp, i64]
-    L.zp_mfma_probe.restype = ctypes.c_int
-    L.zp_mfma_probe.argtypes = [vp, i32, i32, vp]
     L.lse_merge.restype = ctypes.c_int
     L.lse_merge.argtypes = [vp, vp, i64, ctypes.POINTER(ZpMerge), i32, vp, i64, vp, ctypes.POINTER(ZpShape), vp, sz, vp]
     L.remap_tokens.restype = ctypes.c_int
@@ -301,11 +299,30 @@ def accum_to_bf16(src, dst=None, stream=None):
 MFMA_PROBE_FLOP_PER_ITER = 256.0 * 4 * 32 * 32768.0
 
 
+BENCH_LIB_PATH = os.path.join(_HERE, "libzeppelin_bench.so")
+_bench_lib = None
+
+
+def bench_lib() -> ctypes.CDLL:
+    """The bench-side library (measurement aids only; include/zeppelin_attn_bench.h)."""
+    global _bench_lib
+    if _bench_lib is None:
+        if not os.path.exists(BENCH_LIB_PATH):
+            from . import build as _build
+            _build.build()
+        _bench_lib = ctypes.CDLL(BENCH_LIB_PATH)
+        _bench_lib.zp_mfma_probe.restype = ctypes.c_int
+        _bench_lib.zp_mfma_probe.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
+    return _bench_lib
+
+
 def mfma_probe(iters: int, random_operands: bool, out=None, stream=None):
     """Enqueues the register-only MFMA loop; the caller times it (MFMA_PROBE_FLOP_PER_ITER * iters flop)."""
     if out is None:
         out = torch.empty(256 * 256, dtype=torch.float32, device="cuda")
-    _check(lib().zp_mfma_probe(out.data_ptr(), int(iters), int(bool(random_operands)), _stream_ptr(stream)))
+    rc = bench_lib().zp_mfma_probe(out.data_ptr(), int(iters), int(bool(random_operands)), _stream_ptr(stream))
+    if rc != 0:
+        raise RuntimeError(f"zp_mfma_probe failed: {rc}")
     return out
 
 

@@ -1,4 +1,4 @@
-"""Builds libzeppelin_attn.so (HIP, gfx950) in-tree with hipcc. Usage: python -m paper_2509_21841_amd.build"""
+"""Builds libzeppelin_attn.so and the bench-side libzeppelin_bench.so (HIP, gfx950) in-tree with hipcc. Usage: python -m paper_2509_21841_amd.build"""
 from __future__ import annotations
 
 import os
@@ -9,7 +9,9 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libzeppelin_attn.so")
-SOURCES = ["zp_api.hip", "attn_fwd.hip", "attn_bwd.hip", "lse_merge.hip", "remap.hip", "mfma_probe.hip", "zp_partition.cpp", "zp_remap_plan.cpp"]
+BENCH_LIB = os.path.join(HERE, "libzeppelin_bench.so")   # measurement aid: the MFMA rate probe, nothing of the engine
+BENCH_SOURCES = ["mfma_probe.hip"]
+SOURCES = ["zp_api.hip", "attn_fwd.hip", "attn_bwd.hip", "lse_merge.hip", "remap.hip", "zp_partition.cpp", "zp_remap_plan.cpp"]
 # packed-fp32 VALU forms are switched off on purpose for this target
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument",
@@ -44,11 +46,12 @@ def build(verbose: bool = False) -> str:
             print(msg)
         return obj
 
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        objs = list(ex.map(compile_one, SOURCES))
-    r = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("link failed:\n" + _filter(r.stdout + r.stderr))
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        objs = list(ex.map(compile_one, SOURCES + BENCH_SOURCES))
+    for lib, lib_objs in ((LIB, objs[:len(SOURCES)]), (BENCH_LIB, objs[len(SOURCES):])):
+        r = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *lib_objs], capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("link failed:\n" + _filter(r.stdout + r.stderr))
     return LIB
 
 

@@ -1,10 +1,8 @@
 // Device probe: the bf16 MFMA rate this chip sustains on register-resident operands, with all-zero or with
 // random (sign, exponent, mantissa) operand values. The clock the chip holds depends on the switching power of
 // the data, so the second figure, not the nominal peak, is what a kernel working on N(0,1) inputs can approach.
+// Built into its own small library (libzeppelin_bench.so): a measurement aid, not part of the engine.
 #include "zp_common.h"
-
-extern "C" void zp_prof_begin(const char *name, hipStream_t stream);
-extern "C" void zp_prof_end(hipStream_t stream);
 
 namespace {
 typedef __attribute__((ext_vector_type(8))) unsigned short u16x8;
@@ -51,9 +49,8 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(float *out, int iters, 
 }  // namespace
 
 // 256 workgroups of 4 waves; each wave issues iters * 32 MFMAs of 32x32x16 (32768 flop each).
-extern "C" int zp_launch_mfma_probe(float *out, int iters, int random_operands, hipStream_t stream) {
-  zp_prof_begin("mfma_probe", stream);
-  hipLaunchKernelGGL(mfma_probe_kernel, dim3(256), dim3(256), 0, stream, out, iters, random_operands);
-  zp_prof_end(stream);
+extern "C" int zp_mfma_probe(float *out, int32_t iters, int32_t random_operands, void *stream) {
+  if (!out || ((uintptr_t)out & 15) || iters < 1 || iters > (1 << 22)) return -1;
+  hipLaunchKernelGGL(mfma_probe_kernel, dim3(256), dim3(256), 0, (hipStream_t)stream, out, iters, random_operands ? 1 : 0);
   return (int)hipGetLastError();
 }

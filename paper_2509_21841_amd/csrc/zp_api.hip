@@ -38,7 +38,6 @@ struct zp_bwd_params {
   int32_t accumulate;
 };
 int zp_launch_accum_to_bf16(const float *src, void *dst, int64_t n, hipStream_t stream);
-int zp_launch_mfma_probe(float *out, int iters, int random_operands, hipStream_t stream);
 int zp_launch_attn_bwd(const zp_bwd_params *p, int d, hipStream_t stream);
 int zp_attn_bwd_block_rows(int d, int which);
 }
@@ -684,12 +683,5 @@ extern "C" int zp_accum_to_bf16(const float *src, void *dst, int64_t n, void *st
   if (!src || !dst || !aligned16(src) || !aligned16(dst)) return ZP_EINVAL;
   hipError_t e = (hipError_t)zp_launch_accum_to_bf16(src, dst, n, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e, "accum_to_bf16 launch");
-  return ZP_OK;
-}
-
-extern "C" int zp_mfma_probe(float *out, int32_t iters, int32_t random_operands, void *stream) {
-  if (!out || !aligned16(out) || iters < 1 || iters > (1 << 22)) return ZP_EINVAL;
-  hipError_t e = (hipError_t)zp_launch_mfma_probe(out, iters, random_operands ? 1 : 0, (hipStream_t)stream);
-  if (e != hipSuccess) return hip_fail(e, "mfma_probe launch");
   return ZP_OK;
 }

@@ -6,7 +6,7 @@ import torch
 import oracle
 from paper_2509_21841_amd import binding as B
 from paper_2509_21841_amd import synth
-from util import assert_close, assert_lse_close, widen
+from util import Checks, StatedBoundNotMet, assert_close, assert_lse_close, widen
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -201,6 +201,38 @@ def test_chunked_then_merged_equals_whole(L, C, Hq, Hkv, d):
     assert_lse_close("merged LSE", widen(lse)[:, t0:t0 + L], rl[:, t0:t0 + L])
 
 
+@pytest.mark.parametrize("L,G,Hq,Hkv,d", [(1000, 4, 4, 2, 128), (333, 2, 2, 2, 64), (70, 8, 2, 1, 128)])
+def test_rank_share_pairs_through_the_kernels(L, G, Hq, Hkv, d):
+    """What ONE ring rank computes (Sec. 3.2: rank r of a ring of G owns chunks r and 2G-1-r of 2G chunks and, over the
+    rounds, sees every KV chunk at or before them): the pairs of zp_chunk_pairs(rank = r) through chunk_attn_partial
+    and lse_merge give exactly the whole-sequence attention rows of that rank's Q chunks and touch no other row."""
+    lengths = [40, L, 25]
+    (q, k, v), cu = make(lengths, Hq, Hkv, d, 61)
+    t0 = int(cu[1])
+    ro, rl = oracle.varlen_attn_fwd(widen(q), widen(k), widen(v), cu)
+    b = oracle.chunk_bounds(L, 2 * G)
+    covered = np.zeros(L, bool)
+    for r in range(G):
+        pairs, merges, rows = B.chunk_pairs(t0, L, 2 * G, rank=r)
+        # the descriptors are the oracle's pairs (qc, kc <= qc) of the two chunks this rank owns
+        want = [(qc, kc) for qc in sorted((r, 2 * G - 1 - r)) for kc in range(qc + 1)]
+        assert [(p.q_pos0, p.k_pos0, p.q_len, p.k_len) for p in pairs] == \
+            [(b[qc], b[kc], b[qc + 1] - b[qc], b[kc + 1] - b[kc]) for qc, kc in want]
+        op, lp = B.chunk_attn_partial(q, k, v, pairs, rows)
+        o = torch.zeros_like(q); lse = torch.zeros((Hq, q.shape[0]), dtype=torch.float32, device=DEV)
+        B.lse_merge(op, lp, merges, o, lse)
+        torch.cuda.synchronize()
+        mine = np.zeros(q.shape[0], bool)
+        for c in (r, 2 * G - 1 - r):
+            mine[t0 + b[c]:t0 + b[c + 1]] = True
+        if mine.any():
+            assert_close(f"rank {r} O", widen(o)[mine], ro[mine])
+            assert_lse_close(f"rank {r} LSE", widen(lse)[:, mine], rl[:, mine])
+        assert not o[torch.from_numpy(~mine).to(DEV)].any() and not lse[:, torch.from_numpy(~mine).to(DEV)].any()
+        covered[mine[t0:t0 + L]] = True
+    assert covered.all()      # the ranks' shares tile the sequence
+
+
 def test_partial_rows_without_visible_keys():
     (q, k, v), cu = make([400], 2, 1, 128, 19)
     pairs = [dict(q_tok0=100, q_len=200, k_tok0=200, k_len=150, q_pos0=100, k_pos0=200, out_row0=3)]
@@ -366,7 +398,10 @@ def test_mfma_probe_runs_and_is_deterministic():
 
 # ---- a whole node's placement on one GPU ----------------------------------------------------------------
 @pytest.mark.parametrize("lengths,P,N,L,Hq,Hkv,d", [
-    ([700, 90, 300, 1500, 64, 200, 33], 4, 1, 800, 4, 2, 128),       # one intra-node ring, local sequences
+    # one intra-node ring, local sequences. The stated max-abs bound is NOT met by dV here: 2 of 739072 elements,
+    # largest 2.15e-2 at |ref| 6.4, where the bf16 output grid alone takes 1.56e-2 of the 2e-2 (everything else passes)
+    pytest.param([700, 90, 300, 1500, 64, 200, 33], 4, 1, 800, 4, 2, 128, marks=pytest.mark.xfail(
+        strict=True, raises=StatedBoundNotMet, reason="stated max-abs bound not met: dV, 2 of 739072 elements, largest 2.15e-2 at |ref| 6.4")),
     ([2600, 150, 400, 90, 1100, 60], 2, 2, 700, 2, 1, 64),           # an inter-node ring over both nodes
     ([100, 200, 50], 4, 1, 400, 2, 2, 64)])                          # everything local
 def test_node_placement_end_to_end(lengths, P, N, L, Hq, Hkv, d):
@@ -389,8 +424,10 @@ def test_node_placement_end_to_end(lengths, P, N, L, Hq, Hkv, d):
     ro, _ = oracle.varlen_attn_fwd(widen(q0), widen(k0), widen(v0), cu0)
     rdq, rdk, rdv = oracle.varlen_attn_bwd(widen(do0), widen(q0), widen(k0), widen(v0), cu0)
     sel = plan.orig[plan.idx]
-    assert_close("O", widen(ob), ro[sel]); assert_close("dQ", widen(dqb), rdq[sel])
-    assert_close("dK", widen(dkb), rdk[sel]); assert_close("dV", widen(dvb), rdv[sel])
     # the balanced layout gives every rank its target share
     from oracle import remap_planner as RP
     assert [int(x) for x in np.asarray(plan.M).sum(axis=1)] == RP.surplus_deficit(plan.A)[0]
+    c = Checks()
+    c.close("O", widen(ob), ro[sel]); c.close("dQ", widen(dqb), rdq[sel])
+    c.close("dK", widen(dkb), rdk[sel]); c.close("dV", widen(dvb), rdv[sel])
+    c.finish()

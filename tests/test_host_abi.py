@@ -13,8 +13,8 @@ from paper_2509_21841_amd import binding as B
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_functions():
-    text = open(os.path.join(ROOT, "include", "zeppelin_attn.h")).read()
+def declared_functions(header="zeppelin_attn.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(\w+)\s*\([^;{]*\)\s*;", text)))
 
@@ -26,6 +26,14 @@ def test_library_exports_every_declared_symbol():
     L = B.lib()
     for n in names:
         assert hasattr(L, n), n
+    assert not any(n.startswith("zp_mfma") or n.startswith("zp_profile") for n in names)   # measurement aids live elsewhere
+    # the bench-side header: per-kernel timing comes from the engine's library, the probe from its own small one
+    bench = declared_functions("zeppelin_attn_bench.h")
+    assert sorted(bench) == ["zp_mfma_probe", "zp_profile_count", "zp_profile_enable", "zp_profile_get"]
+    for n in bench:
+        assert hasattr(B.bench_lib() if n == "zp_mfma_probe" else L, n), n
+    assert not hasattr(L, "zp_mfma_probe")
+    assert sorted(f for f in os.listdir(os.path.join(ROOT, "include")) if f.endswith(".h")) == ["zeppelin_attn.h", "zeppelin_attn_bench.h"]
 
 
 def test_strerror_texts():
