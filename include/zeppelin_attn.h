@@ -38,6 +38,7 @@ extern "C" {
 #define ZP_EUNSUPPORTED (-2) /* head_dim not 64/128, Hq % Hkv != 0, row_bytes % 16 != 0 */
 #define ZP_EWORKSPACE (-3)   /* ws is NULL, misaligned or smaller than zp_workspace_bytes() */
 #define ZP_EHIP (-4)         /* a HIP runtime call failed; zp_strerror(ZP_EHIP) carries its text */
+#define ZP_ETOOLARGE (-5)    /* more sequences or tiles than the fixed limits of varlen_attn_fwd_noalloc */
 
 #define ZP_MAX_PARTS 16
 
@@ -82,6 +83,22 @@ size_t zp_workspace_bytes(int which_fn, const zp_shape *sh, const int32_t *cu_se
 int varlen_attn_fwd(const void *q, const void *k, const void *v, int64_t q_stride, int64_t k_stride, int64_t v_stride,
                     const int32_t *cu_seqlens_host, const uint8_t *seq_skip_host, void *o, int64_t o_stride, float *lse,
                     const zp_shape *sh, void *ws, size_t ws_bytes, void *stream);
+
+/* varlen_attn_fwd for callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc. Same arguments and same results (bit for bit) as varlen_attn_fwd without the workspace: the tile
+ * table lives in a fixed device array inside the library (ZP_NOALLOC_MAX_TILES records of 32 bytes = 256 KiB, one copy
+ * per GPU, held until the process ends) and is built on the device from the sequence boundaries, which travel by value
+ * in the launch arguments. The call allocates nothing on host or device, reads no host memory from the device and
+ * uploads nothing; it enqueues two kernels on `stream`. Limits: S <= ZP_NOALLOC_MAX_SEQS sequences and at most
+ * ZP_NOALLOC_MAX_TILES blocks of 128 query rows (sum over unflagged sequences of ceil(len / 128)); beyond them the
+ * call returns ZP_ETOOLARGE and enqueues nothing. Every call on a GPU uses that GPU's one table: calls on the same GPU
+ * must be ordered on one stream (or otherwise not overlap), else they race. Keep zp_profile_enable off around it
+ * (the timing aid creates events). */
+#define ZP_NOALLOC_MAX_SEQS 768
+#define ZP_NOALLOC_MAX_TILES 8192
+int varlen_attn_fwd_noalloc(const void *q, const void *k, const void *v, int64_t q_stride, int64_t k_stride,
+                            int64_t v_stride, const int32_t *cu_seqlens_host, const uint8_t *seq_skip_host, void *o,
+                            int64_t o_stride, float *lse, const zp_shape *sh, void *stream);
 
 /* Backward of varlen_attn_fwd (Sec. 5.4: the backward mirrors the forward with about twice the work).
  * Reads dO, Q, K, V and the forward's O and LSE; writes dQ [T][Hq][d], dK, dV [T][Hkv][d] (bf16). With

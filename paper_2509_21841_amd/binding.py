@@ -65,6 +65,8 @@ def lib() -> ctypes.CDLL:
     L.zp_workspace_bytes.argtypes = [ctypes.c_int, ctypes.POINTER(ZpShape), vp, i64]
     L.varlen_attn_fwd.restype = ctypes.c_int
     L.varlen_attn_fwd.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp, vp, i64, vp, ctypes.POINTER(ZpShape), vp, sz, vp]
+    L.varlen_attn_fwd_noalloc.restype = ctypes.c_int
+    L.varlen_attn_fwd_noalloc.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp, vp, i64, vp, ctypes.POINTER(ZpShape), vp]
     L.varlen_attn_bwd.restype = ctypes.c_int
     L.varlen_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, vp, vp, vp, vp, vp, i64, i64,
                                   ctypes.POINTER(ZpShape), vp, sz, vp]
@@ -175,6 +177,25 @@ def varlen_attn_fwd(q, k, v, cu_seqlens, o=None, lse=None, scale=0.0, ws=None, s
     _check(lib().varlen_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), _tok_stride(q), _tok_stride(k), _tok_stride(v),
                                  cu.ctypes.data_as(ctypes.c_void_p), skp, o.data_ptr(), _tok_stride(o), lse.data_ptr(),
                                  ctypes.byref(sh), ws.data_ptr(), ws.numel(), _stream_ptr(stream)))
+    return o, lse
+
+
+NOALLOC_MAX_SEQS, NOALLOC_MAX_TILES = 768, 8192
+
+
+def varlen_attn_fwd_noalloc(q, k, v, cu_seqlens, o, lse, scale=0.0, stream=None, seq_skip=None):
+    """varlen_attn_fwd through the entry point that allocates nothing: the caller brings o and lse, there is no
+    workspace (the tile table is a fixed device array inside the library)."""
+    cu = _cu_host(cu_seqlens)
+    T, Hq, d = q.shape
+    Hkv = k.shape[1]
+    sh = make_shape(T, len(cu) - 1, Hq, Hkv, d, scale)
+    skip = None if seq_skip is None else np.ascontiguousarray(seq_skip, dtype=np.uint8)
+    assert skip is None or len(skip) == len(cu) - 1
+    skp = None if skip is None else skip.ctypes.data_as(ctypes.c_void_p)
+    _check(lib().varlen_attn_fwd_noalloc(q.data_ptr(), k.data_ptr(), v.data_ptr(), _tok_stride(q), _tok_stride(k),
+                                         _tok_stride(v), cu.ctypes.data_as(ctypes.c_void_p), skp, o.data_ptr(),
+                                         _tok_stride(o), lse.data_ptr(), ctypes.byref(sh), _stream_ptr(stream)))
     return o, lse
 
 

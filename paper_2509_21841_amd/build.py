@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libzeppelin_attn.so")
 BENCH_LIB = os.path.join(HERE, "libzeppelin_bench.so")   # measurement aid: the MFMA rate probe, nothing of the engine
 BENCH_SOURCES = ["mfma_probe.hip"]
-SOURCES = ["zp_api.hip", "attn_fwd.hip", "attn_bwd.hip", "lse_merge.hip", "remap.hip", "zp_partition.cpp", "zp_remap_plan.cpp"]
+SOURCES = ["zp_api.hip", "zp_noalloc.hip", "attn_fwd.hip", "attn_bwd.hip", "lse_merge.hip", "remap.hip", "zp_partition.cpp", "zp_remap_plan.cpp"]
 # packed-fp32 VALU forms are switched off on purpose for this target
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument",

@@ -228,6 +228,9 @@ int zp_profile_get(int i, char *name, int name_cap, float *ms) {
   return ZP_OK;
 }
 
+// for the other translation units of the library: records the HIP error text and returns ZP_EHIP
+int zp_report_hip_error(int hip_error, const char *what) { return hip_fail((hipError_t)hip_error, what); }
+
 const char *zp_strerror(int code) {
   switch (code) {
     case ZP_OK: return "ok";
@@ -235,6 +238,7 @@ const char *zp_strerror(int code) {
     case ZP_EUNSUPPORTED: return "unsupported configuration";
     case ZP_EWORKSPACE: return "workspace missing, misaligned or too small";
     case ZP_EHIP: return g_hip_error.c_str();
+    case ZP_ETOOLARGE: return "more sequences or tiles than the fixed limits of the no-allocation entry point";
     default: return "unknown error code";
   }
 }

@@ -153,6 +153,28 @@ def test_table2_length_mixes():
         assert np.abs(hist - want).max() < 0.02, (name, hist, want)
 
 
+def test_noalloc_forward_rejects_oversize_batches_without_device():
+    """The fixed limits of the entry point that allocates nothing are checked on the host, before the device is touched."""
+    L = B.lib()
+
+    def rc(sh, cu, skip=None):
+        cu = np.ascontiguousarray(cu, np.int32)
+        sk = None if skip is None else np.ascontiguousarray(skip, np.uint8).ctypes.data_as(ctypes.c_void_p)
+        return L.varlen_attn_fwd_noalloc(1 << 12, 1 << 12, 1 << 12, sh.Hq * sh.d, sh.Hkv * sh.d, sh.Hkv * sh.d,
+                                         cu.ctypes.data_as(ctypes.c_void_p), sk, 1 << 12, sh.Hq * sh.d, 1 << 12,
+                                         ctypes.byref(sh), None)
+
+    S = B.NOALLOC_MAX_SEQS + 1
+    assert rc(B.make_shape(S, S, 4, 2, 64), np.arange(S + 1)) == -5                    # too many sequences
+    T = (B.NOALLOC_MAX_TILES + 1) * 128
+    assert rc(B.make_shape(T, 1, 4, 2, 64), [0, T]) == -5                              # too many tiles
+    assert rc(B.make_shape(T, 2, 4, 2, 64), [0, 128, T], skip=[1, 1]) == 0             # flagged sequences do not count (nothing left: no-op)
+    assert rc(B.make_shape(100, 2, 4, 2, 64), [0, 60, 40]) == -1                       # the ordinary checks still run
+    assert rc(B.make_shape(100, 2, 4, 2, 96), [0, 40, 100]) == -2
+    assert rc(B.make_shape(0, 1, 4, 2, 64), [0, 0]) == 0
+    assert len(L.zp_strerror(-5)) > 10
+
+
 def _pair_tuple(p):
     return tuple(getattr(p, f) if not isinstance(p, dict) else p[f] for f in ("q_tok0", "q_len", "k_tok0", "k_len", "q_pos0", "k_pos0"))
 
