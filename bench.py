@@ -206,11 +206,24 @@ class NodeBenchJob:
         j.to_balanced(dq, self.dq_lin); j.to_balanced(dk, self.dk_lin); j.to_balanced(dv, self.dv_lin)
 
 
+DKDV_SHORT_ITERATIONS = 128   # the library's routing rule (head dimension 128): see short_sequence()
+
+
+def short_sequence(L: int, grp: int, d: int) -> bool:
+    """True if the library runs the dK/dV work of a whole sequence of L tokens in its kernel for short sequences (two
+    workgroups per CU): fewer than 128 (64-query tile, head) iterations for the sequence's first key block."""
+    return d == 128 and ((L + 63) // 64) * grp < DKDV_SHORT_ITERATIONS
+
+
 def kernel_flops(job, label: str) -> float:
     """Algorithmic FLOPs one step spends in a kernel (2 FLOP per multiply-add over unmasked pairs)."""
     d, Hq = job.w["d"], job.w["Hq"]
     per_gemm_all = 2 * d * Hq * job.pairs_total
     per_gemm_long = 2 * d * Hq * job.pairs_long
+    if label in ("attn_bwd_dkdv", "attn_bwd_dkdv_short") and not hasattr(job, "plan"):
+        grp = Hq // job.w["Hkv"]
+        short = 2 * d * Hq * pairs_of([L for L in job.lengths if short_sequence(L, grp, d)])
+        return 4 * (short if label.endswith("_short") else per_gemm_all - short)
     return {"attn_fwd": 2 * (per_gemm_all - per_gemm_long), "attn_fwd_partial": 2 * per_gemm_long,
             "attn_bwd_dq": 3 * per_gemm_all, "attn_bwd_dkdv": 4 * per_gemm_all}.get(label, 0.0)
 
@@ -303,7 +316,7 @@ def measure(job, steps: int, warmup: int):
 
 def fwd_bwd_rates(job, kern):
     fwd_ms = sum(kern[k]["ms_per_step"] for k in ("attn_fwd", "attn_fwd_partial", "lse_merge") if k in kern)
-    bwd_ms = sum(kern[k]["ms_per_step"] for k in ("attn_bwd_dq", "attn_bwd_dkdv") if k in kern)
+    bwd_ms = sum(kern[k]["ms_per_step"] for k in ("attn_bwd_dq", "attn_bwd_dkdv", "attn_bwd_dkdv_short") if k in kern)
     return (job.flops_fwd / (fwd_ms * 1e-3) / 1e12 if fwd_ms else None,
             job.flops_bwd / (bwd_ms * 1e-3) / 1e12 if bwd_ms else None)
 

@@ -74,9 +74,10 @@ size_t zp_workspace_bytes(int which_fn, const zp_shape *sh, const int32_t *cu_se
 
 /* Causal softmax attention of every sequence of the packed batch (Sec. 3.2, local sequences; Sec. 2.1):
  *   O[i,h,:] = sum_{j<=i} softmax_j(scale q_i.k_j) v_j ,   LSE[h,i] = log sum_{j<=i} exp(scale q_i.k_j).
- * The host builds a work list of (sequence, query block) tiles ordered by descending number of visible
- * key tiles -- the quadratic cost model |s|^2 of Alg. 2 applied per tile -- so that the heaviest tiles
- * start first and the light tail fills the gaps.
+ * The host builds a work list of (sequence, query block) tiles by the quadratic cost model |s|^2 of Alg. 2:
+ * sequences in descending length and, inside a sequence, query blocks in descending number of visible key
+ * tiles, so that the heaviest tiles of the batch start first, the light ones fill the tail, and the blocks
+ * of one sequence run side by side and share its K/V rows in the cache.
  * q,k,v: device bf16; o: device bf16 out; lse: device float32 [Hq][T] out; cu_seqlens_host: host [S+1].
  * seq_skip_host: NULL, or host [S] flags; a flagged sequence is left out (its O / LSE rows are not written)
  * so that the caller can compute it as chunk pairs instead (Sec. 3.2: ring sequences vs local sequences). */

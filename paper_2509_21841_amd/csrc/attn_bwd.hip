@@ -17,7 +17,8 @@ struct zp_bwd_params {
   float *lse2;        // [Hq][T] scratch: -LSE_i / scale
   const zp_tile *dq_tiles;
   const zp_tile *kv_tiles;
-  int32_t n_dq_tiles, n_kv_tiles, Hq, Hkv, grp, T;
+  const zp_tile *kv_tiles_short;  // key blocks with few query tiles: run by the two-workgroups-per-CU kernel (d = 128)
+  int32_t n_dq_tiles, n_kv_tiles, n_kv_tiles_short, Hq, Hkv, grp, T;
   float scale_log2, scale;
   __bf16 *dq, *dk, *dv;      // outputs (bf16, overwritten) ...
   int64_t dq_stride, dkv_stride;
@@ -527,6 +528,266 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(D == 64 
   }
 }
 
+// ---------------------------------------------------------------------------- dK, dV at head dimension 128
+// The LDS read addresses of zp_lds_offsets with three registers instead of sixteen: the swizzle XORs the 16-byte
+// chunk index with a function of the row, so the offsets of the k-steps (row pattern) and of the 32-column blocks
+// (transposed pattern) differ from the first one by an XOR with a constant -- also after a multiple of 256 bytes
+// (tile, row block) has been added.
+struct dkdv_lds_addr {
+  unsigned row0, tr0[2];
+  __device__ __forceinline__ void init(int lane) {
+    zp_lds_offsets<128> lo;
+    lo.init(lane);
+    row0 = lo.row_off[0]; tr0[0] = lo.tr_off[0][0]; tr0[1] = lo.tr_off[1][0];
+  }
+  // base = LDS address of the tile + the lane's first offset + the row block, see rows_base / tr_base
+  __device__ __forceinline__ unsigned rows_base(const char *tile, int blk) const { return zp_lds_addr(tile) + row0 + blk * 32 * 256; }
+  static __device__ __forceinline__ bf16x8 rows(unsigned base, int kk) {
+    return *(const ZP_LDS bf16x8 *)(unsigned long long)(base ^ (unsigned)(kk << 5));
+  }
+  __device__ __forceinline__ unsigned tr_base(const char *tile, int blk, int j) const { return zp_lds_addr(tile) + tr0[j] + blk * 32 * 256; }
+  static __device__ __forceinline__ bf16x8 tr(unsigned b0, unsigned b1, int m, int db) {
+    const unsigned o = (unsigned)(db << 6);
+    s16x4 u0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ZP_LDS s16x4 *)(unsigned long long)((b0 ^ o) + m * 16 * 256));
+    s16x4 u1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ZP_LDS s16x4 *)(unsigned long long)((b1 ^ o) + m * 16 * 256));
+    return zp_cat(__builtin_bit_cast(bf16x4, u0), __builtin_bit_cast(bf16x4, u1));
+  }
+};
+
+template <int D, bool MASK, bool PIECES, class Piece>
+__device__ __forceinline__ void dkdv_block(const char *Qb, const char *Ob, const float *Lb, const float *Db, int qb,
+                                           const bf16x8 (&kreg)[D / 16], const char *Vt, int vkb,
+                                           f32x16 (&dk_acc)[D / 32], f32x16 (&dv_acc)[D / 32], int qpos0, int kpos,
+                                           int qpos_end, float c_log2, int hi, const dkdv_lds_addr &la,
+                                           Piece &&piece) {
+  constexpr int KK = D / 16, DB = D / 32;
+  f32x16 s, dp;
+#pragma unroll
+  for (int b = 0; b < 4; b++) {  // -LSE/scale and -D of the 16 query rows this lane holds
+    const f32x4 l4 = *(const ZP_LDS f32x4 *)((const ZP_LDS char *)Lb + (qb * 32 + 8 * b + 4 * hi) * 4);
+    const f32x4 d4 = *(const ZP_LDS f32x4 *)((const ZP_LDS char *)Db + (qb * 32 + 8 * b + 4 * hi) * 4);
+#pragma unroll
+    for (int c = 0; c < 4; c++) { s[4 * b + c] = l4[c]; dp[4 * b + c] = d4[c]; }
+  }
+  // Four runs of eight MFMAs -- S, dP, dV^T, dK^T -- each a fenced pipeline with its LDS operands two steps ahead;
+  // the last two steps of a run request the first operands of the next one. One run at a time keeps the operands in
+  // flight at 24 registers (all four streams two steps ahead would not fit beside the accumulators). The empty asm
+  // in every step keeps the compiler from working out all the addresses of a run ahead of it.
+  unsigned xb = la.rows_base(Qb, qb), yb = la.rows_base(Ob, qb), vb = la.rows_base(Vt, vkb);
+  unsigned xt0 = la.tr_base(Ob, qb, 0), xt1 = la.tr_base(Ob, qb, 1), yt0 = la.tr_base(Qb, qb, 0), yt1 = la.tr_base(Qb, qb, 1);
+  bf16x8 x[KK], y[KK], v[KK], xt[2 * DB], yt[2 * DB];
+  x[0] = la.rows(xb, 0); x[1] = la.rows(xb, 1);
+  zp_static_for<KK>([&](auto kk) {
+    constexpr int k = kk.value;
+    __builtin_amdgcn_sched_barrier(0);
+    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x[k], kreg[k], s, 0, 0, 0);
+    asm volatile("" : "+v"(xb), "+v"(yb), "+v"(vb));
+    if constexpr (k + 2 < KK) x[k + 2] = la.rows(xb, k + 2);
+    else { y[k + 2 - KK] = la.rows(yb, k + 2 - KK); v[k + 2 - KK] = la.rows(vb, k + 2 - KK); }
+    if constexpr (PIECES) piece(kk);
+  });
+  zp_static_for<KK>([&](auto kk) {
+    constexpr int k = kk.value;
+    __builtin_amdgcn_sched_barrier(0);
+    dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(y[k], v[k], dp, 0, 0, 0);
+    asm volatile("" : "+v"(yb), "+v"(vb), "+v"(xt0), "+v"(xt1));
+    if constexpr (k + 2 < KK) { y[k + 2] = la.rows(yb, k + 2); v[k + 2] = la.rows(vb, k + 2); }
+    else xt[k + 2 - KK] = la.tr(xt0, xt1, (k + 2 - KK) / DB, (k + 2 - KK) % DB);
+  });
+  __builtin_amdgcn_sched_barrier(0);
+  unsigned ppk[8], dpk[8];
+#pragma unroll
+  for (int q = 0; q < 8; q++) dkdv_pair<MASK>(s, dp, 2 * q, qb, hi, qpos0, kpos, qpos_end, c_log2, ppk[q], dpk[q]);
+  const bf16x8 pb[2] = {__builtin_bit_cast(bf16x8, (u32x4){ppk[0], ppk[1], ppk[2], ppk[3]}),
+                        __builtin_bit_cast(bf16x8, (u32x4){ppk[4], ppk[5], ppk[6], ppk[7]})};
+  const bf16x8 dsb[2] = {__builtin_bit_cast(bf16x8, (u32x4){dpk[0], dpk[1], dpk[2], dpk[3]}),
+                         __builtin_bit_cast(bf16x8, (u32x4){dpk[4], dpk[5], dpk[6], dpk[7]})};
+  zp_static_for<2 * DB>([&](auto ii) {
+    constexpr int i = ii.value, m = i / DB, db = i % DB;
+    __builtin_amdgcn_sched_barrier(0);
+    dv_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xt[i], pb[m], dv_acc[db], 0, 0, 0);
+    asm volatile("" : "+v"(xt0), "+v"(xt1), "+v"(yt0), "+v"(yt1));
+    if constexpr (i + 2 < 2 * DB) xt[i + 2] = la.tr(xt0, xt1, (i + 2) / DB, (i + 2) % DB);
+    else yt[i + 2 - 2 * DB] = la.tr(yt0, yt1, (i + 2 - 2 * DB) / DB, (i + 2 - 2 * DB) % DB);
+  });
+  zp_static_for<2 * DB>([&](auto ii) {
+    constexpr int i = ii.value, m = i / DB, db = i % DB;
+    __builtin_amdgcn_sched_barrier(0);
+    dk_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(yt[i], dsb[m], dk_acc[db], 0, 0, 0);
+    asm volatile("" : "+v"(yt0), "+v"(yt1));
+    if constexpr (i + 2 < 2 * DB) yt[i + 2] = la.tr(yt0, yt1, (i + 2) / DB, (i + 2) % DB);
+  });
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+
+#ifndef ZP_DKDV_NBUF
+#define ZP_DKDV_NBUF 2
+#endif
+// Two waves per SIMD for head dimension 128 as well: two independent workgroups of four waves per CU (80 KB of LDS
+// each), a wave holding its K operands (32 registers) and its dK^T/dV^T accumulators (128) and working on 32-query
+// tiles, one block's S and dP at a time; the V operands do not fit beside them in 256 registers and are read from
+// LDS, where the workgroup's 128 V rows are staged once. An MFMA takes about 20 cycles of its wave's vector issue
+// time and the wave's LDS, scalar and wait instructions issue in line with it; a second wave on the SIMD, from a
+// workgroup that meets its own barriers, runs under all of that.
+__global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dkdv128_kernel(zp_bwd_params p) {
+  constexpr int D = 128, QT = 32;
+  constexpr int TILEB = QT * D * 2;                // a staged tile: 32 query rows
+  constexpr int NBUF = ZP_DKDV_NBUF;               // staging buffers (three would not fit two workgroups per CU with the seeds)
+  typedef zp_stager<D, 8> stager;                  // 4 waves x 2 wave-loads = the first 32 rows of its 64-row pattern
+  constexpr int PW = stager::PER_WAVE;
+  constexpr int LOADS = 2 * PW + 2;                // async loads one wave issues per staged tile
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  char *Qs = smem;                                 // [NBUF][32][D]
+  char *Os = smem + NBUF * TILEB;                  // [NBUF][32][D]  (dO)
+  char *Vs = smem + 2 * NBUF * TILEB;              // [2][64][D]: the workgroup's V rows, staged once
+  float *Ls = (float *)(Vs + 2 * 64 * D * 2);      // [NBUF][32] -LSE / scale
+  float *Ds = Ls + NBUF * QT;                      // [NBUF][32] -D
+
+  const int unit = blockIdx.x;
+  if (unit >= p.n_kv_tiles_short * p.Hkv) return;
+  const int tile_idx = unit / p.Hkv, g = unit - tile_idx * p.Hkv;
+  const zp_tile t = p.kv_tiles_short[tile_idx];
+
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int kl = lane & 31, hi = lane >> 5;
+  const int krow = w * 32 + kl;
+  const bool key_ok = krow < t.k_len;
+  const int64_t ktok = (int64_t)t.k_tok0 + krow;
+  const int kpos = t.k_pos0 + krow;
+
+  // K operands in registers; V operands from LDS (rows past the block's last key repeat it: a key column never
+  // mixes with another, and those columns are not stored)
+  bf16x8 kreg[D / 16];
+  {
+    const __bf16 *kp = p.k + ktok * p.k_stride + (int64_t)g * D + 8 * hi;
+#pragma unroll
+    for (int kk = 0; kk < D / 16; kk++) {
+      if (key_ok) kreg[kk] = *(const bf16x8 *)(kp + 16 * kk);
+      else kreg[kk] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+    }
+  }
+
+  f32x16 dk_acc[D / 32], dv_acc[D / 32];
+#pragma unroll
+  for (int i = 0; i < D / 32; i++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) { dk_acc[i][r] = 0.f; dv_acc[i][r] = 0.f; }
+  const float c_log2 = p.scale_log2;
+
+  const int n_qt = (t.q_rows + QT - 1) / QT;
+  const int n_it = n_qt * p.grp;  // iterations: query tiles outermost (last tile first), heads of the group innermost
+
+  stager qst, ost;
+  qst.init(p.q + (int64_t)t.q_tok0 * p.q_stride + (int64_t)g * p.grp * D, p.q_stride, tid);
+  ost.init(p.dout + (int64_t)t.q_tok0 * p.do_stride + (int64_t)g * p.grp * D, p.do_stride, tid);
+  dkdv_lds_addr la;
+  la.init(lane);
+  {
+    zp_stager<D> vst;
+    vst.init(p.v + (int64_t)t.k_tok0 * p.v_stride + (int64_t)g * D, p.v_stride, tid);
+    vst.issue(Vs, 0, t.k_len);
+    vst.issue(Vs + 64 * D * 2, 64, t.k_len);
+  }
+  const char *Vt = Vs + (w >> 1) * (64 * D * 2);
+  const int vkb = w & 1;
+  // 32 floats of a row vector, one per lane of the lower half-wave (rows past the last valid one repeat it)
+  auto stage_f32x32 = [&](float *dst, const float *src, int first, int last_valid) {
+    int i = first + (lane & 31);
+    if (i > last_valid) i = last_valid;
+    if (lane < 32) zp_dma4(src + i, __builtin_amdgcn_readfirstlane(zp_lds_addr(dst)));
+  };
+  int st_hh = 0, st_qt = n_qt - 1;
+  auto stage = [&](int buf) {
+    const int hh = st_hh, i0 = st_qt * QT;
+    const int h = g * p.grp + hh;
+    if (++st_hh == p.grp) { st_hh = 0; st_qt--; }
+    qst.issue(Qs + buf * TILEB, i0, t.q_rows, (int64_t)hh * D);
+    ost.issue(Os + buf * TILEB, i0, t.q_rows, (int64_t)hh * D);
+    const int64_t base = (int64_t)h * p.T + t.q_tok0;
+    stage_f32x32(Ls + buf * QT, p.lse2 + base, i0, t.q_rows - 1);
+    stage_f32x32(Ds + buf * QT, p.dvec + base, i0, t.q_rows - 1);
+  };
+  // the same copies for a tile of 32 valid rows, one per k-step of the S chain (piece 0: the scalar addresses)
+  const void *pc_q = nullptr, *pc_o = nullptr, *pc_l = nullptr, *pc_d = nullptr;
+  unsigned pc_buf = 0;
+  auto stage_piece = [&](auto n) {
+    constexpr int N = decltype(n)::value;
+    static_assert(2 * PW + 3 <= D / 16, "the copies of a tile fit the steps of one chain");
+    if constexpr (N == 0) {
+      const int hh = st_hh, i0 = st_qt * QT;
+      const int h = g * p.grp + hh;
+      if (++st_hh == p.grp) { st_hh = 0; st_qt--; }
+      pc_q = zp_uniform_ptr(qst.base + (int64_t)i0 * qst.stride + (int64_t)hh * D);
+      pc_o = zp_uniform_ptr(ost.base + (int64_t)i0 * ost.stride + (int64_t)hh * D);
+      const int64_t base = (int64_t)h * p.T + t.q_tok0 + i0;
+      pc_l = zp_uniform_ptr(p.lse2 + base);
+      pc_d = zp_uniform_ptr(p.dvec + base);
+    } else if constexpr (N <= PW) {
+      zp_dma16_so(pc_q, qst.off[N - 1], __builtin_amdgcn_readfirstlane(zp_lds_addr(Qs) + pc_buf * TILEB + (qst.w * PW + N - 1) * 1024));
+    } else if constexpr (N <= 2 * PW) {
+      zp_dma16_so(pc_o, ost.off[N - PW - 1], __builtin_amdgcn_readfirstlane(zp_lds_addr(Os) + pc_buf * TILEB + (ost.w * PW + N - PW - 1) * 1024));
+    } else if constexpr (N == 2 * PW + 1) {
+      if (lane < 32) zp_dma4_so(pc_l, lane * 4, __builtin_amdgcn_readfirstlane(zp_lds_addr(Ls) + pc_buf * (QT * 4)));
+    } else if constexpr (N == 2 * PW + 2) {
+      if (lane < 32) zp_dma4_so(pc_d, lane * 4, __builtin_amdgcn_readfirstlane(zp_lds_addr(Ds) + pc_buf * (QT * 4)));
+    }
+  };
+  auto no_piece = [](auto) {};
+
+  if (n_it > 0) stage(0);
+  zp_wait_async();
+#pragma unroll
+  for (int b = 1; b < NBUF - 1; b++)
+    if (n_it > b) stage(b);
+  __syncthreads();
+
+  const int kpos_w_min = t.k_pos0 + w * 32, kpos_w_max = t.k_pos0 + w * 32 + 31;
+  const int qpos_end = t.q_pos0 + t.q_rows;
+
+  int buf = 0, cur_qt = n_qt - 1, cur_hh = 0;
+  for (int it = 0; it < n_it; it++) {
+    const int i0 = cur_qt * QT;
+    if (++cur_hh == p.grp) { cur_hh = 0; cur_qt--; }
+    const int ahead = n_it - 1 - it;        // tiles after this one
+    const int qpos0 = t.q_pos0 + i0;        // position of the tile's first query
+    const bool compute = qpos0 + QT - 1 >= kpos_w_min;  // otherwise every query of the tile precedes every key of this wave
+    const bool masked = qpos0 < kpos_w_max || qpos0 + QT > qpos_end;
+    // the tile NBUF - 1 iterations ahead is fetched inside this tile's S chain when it is a full tile and this wave
+    // computes an unmasked one (the common case), else in front
+    const bool fetch = ahead >= NBUF - 1;
+    const bool fused = fetch && compute && !masked && st_qt * QT + QT <= t.q_rows;
+    pc_buf = buf == 0 ? NBUF - 1 : buf - 1;
+    if (fetch && !fused) stage(pc_buf);
+
+    if (compute) {
+      const char *Qb = Qs + buf * TILEB;
+      const char *Ob = Os + buf * TILEB;
+      if (masked)
+        dkdv_block<D, true, false>(Qb, Ob, Ls + buf * QT, Ds + buf * QT, 0, kreg, Vt, vkb, dk_acc, dv_acc, qpos0, kpos, qpos_end, c_log2, hi, la, no_piece);
+      else if (fused)
+        dkdv_block<D, false, true>(Qb, Ob, Ls + buf * QT, Ds + buf * QT, 0, kreg, Vt, vkb, dk_acc, dv_acc, qpos0, kpos, qpos_end, c_log2, hi, la, stage_piece);
+      else
+        dkdv_block<D, false, false>(Qb, Ob, Ls + buf * QT, Ds + buf * QT, 0, kreg, Vt, vkb, dk_acc, dv_acc, qpos0, kpos, qpos_end, c_log2, hi, la, no_piece);
+    }
+    // the next tile must have landed; the one behind it may stay in flight
+    if (ahead >= NBUF - 1) zp_wait_async_upto<(NBUF - 2) * LOADS>();
+    else zp_wait_async();
+    __syncthreads();
+    buf = buf + 1 == NBUF ? 0 : buf + 1;
+  }
+
+  if (key_ok) {
+    if (p.accumulate) {
+      add_acc_rows<D>((float *)p.dk + ktok * p.dkv_stride + (int64_t)g * D + 4 * hi, dk_acc, p.scale);
+      add_acc_rows<D>((float *)p.dv + ktok * p.dkv_stride + (int64_t)g * D + 4 * hi, dv_acc, 1.0f);
+    } else {
+      store_acc_rows<D>(p.dk + ktok * p.dkv_stride + (int64_t)g * D + 4 * hi, dk_acc, p.scale);
+      store_acc_rows<D>(p.dv + ktok * p.dkv_stride + (int64_t)g * D + 4 * hi, dv_acc, 1.0f);
+    }
+  }
+}
+
 }  // namespace
 
 extern "C" void zp_prof_begin(const char *name, hipStream_t stream);
@@ -550,6 +811,15 @@ extern "C" int zp_launch_attn_bwd(const zp_bwd_params *p, int d, hipStream_t str
     zp_prof_begin("attn_bwd_dkdv", stream);
     if (d == 128) hipLaunchKernelGGL((attn_bwd_dkdv_kernel<128>), dim3(kv_units), dim3(BWD_NT), 8 * 64 * 128 * 2 + 2048, stream, *p);
     else hipLaunchKernelGGL((attn_bwd_dkdv_kernel<64>), dim3(kv_units), dim3(BWD_NT), 8 * 64 * 64 * 2 + 2048, stream, *p);
+    zp_prof_end(stream);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return (int)e;
+  }
+  const int kv_units_short = p->n_kv_tiles_short * p->Hkv;   // only ever non-zero at d = 128
+  if (kv_units_short > 0) {
+    zp_prof_begin("attn_bwd_dkdv_short", stream);
+    hipLaunchKernelGGL(attn_bwd_dkdv128_kernel, dim3(kv_units_short), dim3(BWD_NT),
+                       2 * ZP_DKDV_NBUF * 32 * 128 * 2 + 2 * 64 * 128 * 2 + 2 * ZP_DKDV_NBUF * 32 * 4, stream, *p);
     zp_prof_end(stream);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;

@@ -149,8 +149,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       else qreg[kk] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
     }
   }
-  // the register operands have arrived before the first asynchronous tile copy is issued
-  zp_wait_async();
+  // No wait here: the first tile copy is issued right behind these loads so that the two memory latencies of the
+  // prologue overlap; the explicit wait in front of the first barrier covers both (and tells the compiler that the
+  // register operands have arrived: a wait of its own inside the key loop would drain the copies in flight).
 
   zp_stager<D> kst, vst;
   kst.init(p.k + (int64_t)t.k_tok0 * p.k_stride + (int64_t)g * D, p.k_stride, tid);

@@ -31,7 +31,8 @@ struct zp_bwd_params {
   float *lse2;
   const zp_tile *dq_tiles;
   const zp_tile *kv_tiles;
-  int32_t n_dq_tiles, n_kv_tiles, Hq, Hkv, grp, T;
+  const zp_tile *kv_tiles_short;  // key blocks with few query tiles: run by the two-workgroups-per-CU kernel (d = 128)
+  int32_t n_dq_tiles, n_kv_tiles, n_kv_tiles_short, Hq, Hkv, grp, T;
   float scale_log2, scale;
   __bf16 *dq, *dk, *dv;
   int64_t dq_stride, dkv_stride;
@@ -131,7 +132,7 @@ float eff_scale(const zp_shape *sh) { return sh->scale > 0.f ? sh->scale : 1.0f 
 
 // ---- planner -------------------------------------------------------------------------------------
 // A tile's cost is the number of key tiles it visits: the per-block share of the quadratic cost |s|^2 that
-// Alg. 2 balances. Tiles are issued in descending cost so the heaviest start first.
+// Alg. 2 balances. Lists of chunk-pair tiles are issued in descending cost so the heaviest start first.
 struct CostTile {
   zp_tile t;
   int32_t cost;
@@ -150,11 +151,19 @@ int64_t count_blocks(const int32_t *cu, int S, int bm) {
   for (int s = 0; s < S; s++) n += ((int64_t)cu[s + 1] - cu[s] + bm - 1) / bm;
   return n;
 }
+// Tiles of whole sequences: sequence by sequence, longest sequence first, and inside a sequence the last query block
+// (the most expensive one) first. The heaviest tiles of the batch still start first and the cheap ones fill the tail,
+// as a plain sort by cost would have it, but the query blocks of one (sequence, KV head) now run next to each other on
+// one XCD and find the sequence's K/V rows in its L2 instead of re-reading them from HBM -- with many short sequences
+// and one KV head per query head that re-reading, not the arithmetic, bounded the kernels.
 void plan_whole(const int32_t *cu, int S, int bm, std::vector<CostTile> &out, const uint8_t *skip = nullptr) {
-  for (int s = 0; s < S; s++) {
+  std::vector<int> seq_order(S);
+  for (int s = 0; s < S; s++) seq_order[s] = s;
+  std::stable_sort(seq_order.begin(), seq_order.end(), [&](int a, int b) { return cu[a + 1] - cu[a] > cu[b + 1] - cu[b]; });
+  for (int s : seq_order) {
     if (skip && skip[s]) continue;
     const int32_t L = cu[s + 1] - cu[s];
-    for (int32_t r0 = 0; r0 < L; r0 += bm) {
+    for (int32_t r0 = ((L - 1) / bm) * bm; L > 0 && r0 >= 0; r0 -= bm) {
       CostTile c;
       c.t.q_tok0 = cu[s] + r0;
       c.t.q_rows = std::min(bm, L - r0);
@@ -168,7 +177,6 @@ void plan_whole(const int32_t *cu, int S, int bm, std::vector<CostTile> &out, co
       out.push_back(c);
     }
   }
-  sort_by_cost(out);
 }
 int64_t count_pair_blocks(const zp_pair *pairs, int n, int bm) {
   int64_t c = 0;
@@ -186,6 +194,18 @@ int upload_tiles(const std::vector<CostTile> &tiles, void *ws, hipStream_t strea
   zp_tile *h = (zp_tile *)host;
   for (size_t i = 0; i < tiles.size(); i++) h[i] = tiles[i].t;
   return pool_upload(slot, host, ws, bytes, stream);
+}
+
+// Sequences (or chunk pairs) whose key blocks loop over few (query tile, head) iterations go to the dK/dV kernel that
+// runs two workgroups per CU (head dimension 128 only): a workgroup's fixed cost -- launch, row operands, first tiles,
+// final stores -- is then covered by its neighbour, which is worth more than the other kernel's denser key loop below
+// about 128 iterations of 64 queries. The choice is made per sequence, not per key block, so that the light last blocks
+// of a long sequence stay in the long kernel's launch and fill its tail.
+inline bool kv_rows_are_short(int64_t q_rows_max, int d, int grp) { return d == 128 && ((q_rows_max + 63) / 64) * grp < 128; }
+// Moves the tiles marked short (aux = 1) behind the others, keeping the order inside both parts; returns the number of
+// long tiles.
+size_t split_kv_tiles(std::vector<CostTile> &kt) {
+  return (size_t)(std::stable_partition(kt.begin(), kt.end(), [](const CostTile &c) { return c.t.aux == 0; }) - kt.begin());
 }
 
 }  // namespace
@@ -551,6 +571,7 @@ extern "C" int varlen_attn_bwd(const void *dout, const void *q, const void *k, c
   for (int s : seq_order) {
     if (seq_skip && seq_skip[s]) continue;
     const int32_t L = cu[s + 1] - cu[s];
+    const int32_t short_rows = kv_rows_are_short(L, sh->d, sh->Hq / sh->Hkv) ? 1 : 0;
     for (int32_t j0 = 0; j0 < L; j0 += bnk) {
       CostTile c;
       c.t.k_tok0 = cu[s] + j0;
@@ -560,12 +581,13 @@ extern "C" int varlen_attn_bwd(const void *dout, const void *q, const void *k, c
       c.t.q_rows = L - j0;
       c.t.q_pos0 = j0;
       c.t.out_row0 = cu[s] + j0;
-      c.t.aux = 0;
+      c.t.aux = short_rows;
       c.cost = (c.t.q_rows + 63) / 64;
       kt.push_back(c);
     }
   }
   if (qt.empty() && kt.empty()) return ZP_OK;
+  const size_t n_kv_long = split_kv_tiles(kt);
   const size_t tile_bytes = align256((qt.size() + kt.size()) * sizeof(zp_tile));
   const size_t dvec_bytes = align256((size_t)sh->Hq * (size_t)sh->T * sizeof(float));
   if ((rc = check_ws(ws, ws_bytes, tile_bytes + 2 * dvec_bytes))) return rc;
@@ -581,7 +603,8 @@ extern "C" int varlen_attn_bwd(const void *dout, const void *q, const void *k, c
   p.lse2 = (float *)((char *)ws + tile_bytes + dvec_bytes);
   p.dq_tiles = (const zp_tile *)ws;
   p.kv_tiles = (const zp_tile *)ws + qt.size();
-  p.n_dq_tiles = (int32_t)qt.size(); p.n_kv_tiles = (int32_t)kt.size();
+  p.n_dq_tiles = (int32_t)qt.size(); p.n_kv_tiles = (int32_t)n_kv_long;
+  p.kv_tiles_short = p.kv_tiles + n_kv_long; p.n_kv_tiles_short = (int32_t)(kt.size() - n_kv_long);
   p.Hq = sh->Hq; p.Hkv = sh->Hkv; p.grp = sh->Hq / sh->Hkv; p.T = sh->T;
   p.scale = eff_scale(sh); p.scale_log2 = p.scale * 1.4426950408889634f;
   p.dq = (__bf16 *)dq; p.dk = (__bf16 *)dk; p.dv = (__bf16 *)dv;
@@ -593,7 +616,7 @@ extern "C" int varlen_attn_bwd(const void *dout, const void *q, const void *k, c
 
 // Builds the dQ tiles (blocks of query rows of each pair's Q chunk against its KV chunk) and the dK/dV tiles (blocks
 // of key rows of each pair's KV chunk against the Q-chunk rows that can see them) of one ring round.
-static void plan_pairs_bwd(const zp_pair *pairs, int n_pairs, int bmq, int bnk, std::vector<CostTile> &qt,
+static void plan_pairs_bwd(const zp_pair *pairs, int n_pairs, int bmq, int bnk, int d, int grp, std::vector<CostTile> &qt,
                            std::vector<CostTile> &kt) {
   for (int i = 0; i < n_pairs; i++) {
     const zp_pair &pr = pairs[i];
@@ -612,7 +635,7 @@ static void plan_pairs_bwd(const zp_pair *pairs, int n_pairs, int bmq, int bnk, 
       CostTile c;
       c.t.k_tok0 = pr.k_tok0 + j0; c.t.k_len = std::min(bnk, pr.k_len - j0); c.t.k_pos0 = pr.k_pos0 + j0;
       c.t.q_tok0 = pr.q_tok0 + off; c.t.q_rows = pr.q_len - off; c.t.q_pos0 = pr.q_pos0 + off;
-      c.t.out_row0 = c.t.k_tok0; c.t.aux = 0;
+      c.t.out_row0 = c.t.k_tok0; c.t.aux = kv_rows_are_short(pr.q_len, d, grp) ? 1 : 0;
       c.cost = (c.t.q_rows + 63) / 64;
       kt.push_back(c);
     }
@@ -654,7 +677,8 @@ extern "C" int chunk_attn_partial_bwd(const void *dout, const void *q, const voi
   }
   const int bmq = zp_attn_bwd_block_rows(sh->d, 0), bnk = zp_attn_bwd_block_rows(sh->d, 1);
   std::vector<CostTile> qt, kt;
-  plan_pairs_bwd(pairs, n_pairs, bmq, bnk, qt, kt);
+  plan_pairs_bwd(pairs, n_pairs, bmq, bnk, sh->d, sh->Hq / sh->Hkv, qt, kt);
+  const size_t n_kv_long = split_kv_tiles(kt);
   const size_t tile_bytes = align256((qt.size() + kt.size()) * sizeof(zp_tile));
   const size_t dvec_bytes = align256((size_t)sh->Hq * (size_t)sh->T * sizeof(float));
   if ((rc = check_ws(ws, ws_bytes, tile_bytes + 2 * dvec_bytes))) return rc;
@@ -670,7 +694,8 @@ extern "C" int chunk_attn_partial_bwd(const void *dout, const void *q, const voi
   p.lse2 = (float *)((char *)ws + tile_bytes + dvec_bytes);
   p.dq_tiles = (const zp_tile *)ws;
   p.kv_tiles = (const zp_tile *)ws + qt.size();
-  p.n_dq_tiles = (int32_t)qt.size(); p.n_kv_tiles = (int32_t)kt.size();
+  p.n_dq_tiles = (int32_t)qt.size(); p.n_kv_tiles = (int32_t)n_kv_long;
+  p.kv_tiles_short = p.kv_tiles + n_kv_long; p.n_kv_tiles_short = (int32_t)(kt.size() - n_kv_long);
   p.Hq = sh->Hq; p.Hkv = sh->Hkv; p.grp = sh->Hq / sh->Hkv; p.T = sh->T;
   p.scale = eff_scale(sh); p.scale_log2 = p.scale * 1.4426950408889634f;
   p.dq = (__bf16 *)dq_acc; p.dk = (__bf16 *)dk_acc; p.dv = (__bf16 *)dv_acc;

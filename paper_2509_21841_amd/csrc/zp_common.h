@@ -161,9 +161,9 @@ __device__ __forceinline__ const void *zp_uniform_ptr(const void *p) {
 // out once (they carry the LDS swizzle); issuing a tile is then scalar address arithmetic plus the loads.
 // `init` takes the tensor base of the row run and the token stride (64 * stride * 2 bytes must fit 32 bits);
 // `issue` copies rows row0 .. row0+63 (rows past rows_total clamp to the last valid row).
-template <int D>
+template <int D, int NW = 4>
 struct zp_stager {
-  static constexpr int PER_WAVE = 64 * D * 2 / 1024 / 4;  // 1 KiB wave-loads per wave (4 waves)
+  static constexpr int PER_WAVE = 64 * D * 2 / 1024 / NW;  // 1 KiB wave-loads per wave (NW = 4: the four waves share a 64-row tile; NW = 8: they cover its first 32 rows)
   static constexpr int LOADS = PER_WAVE;
   unsigned off[PER_WAVE];  // bytes from the tile's first row
   int64_t stride;

@@ -1,4 +1,4 @@
-// varlen_attn_fwd for callers that cannot allocate or upload: the cost-sorted tile table of the forward kernel is
+// varlen_attn_fwd for callers that cannot allocate or upload: the ordered tile table of the forward kernel is
 // built ON the device, from sequence boundaries passed by value in the launch arguments, into a file-scope device
 // array. Nothing is allocated, no host buffer is read by the device, so the call can sit under HIP graph capture or in
 // a serving loop that forbids hipMalloc. The attention kernel itself is the one varlen_attn_fwd launches.
@@ -31,24 +31,23 @@ struct PlanArgs {
 };
 static_assert(sizeof(PlanArgs) + sizeof(void *) <= 4096, "kernel arguments are limited to 4 KB");
 
-// Blocks of sequence s: full blocks cost 2, 4, 6, ... key tiles of 64 (block b sees keys 0 .. 128 b + 127), a ragged
-// last block costs ceil(L / 64). Costs inside a sequence are distinct and ascending.
-__device__ __forceinline__ void seq_blocks(const PlanArgs &a, int s, int &L, int &n_full, int &tail_cost) {
+// Query blocks of sequence s (none if it is flagged).
+__device__ __forceinline__ void seq_blocks(const PlanArgs &a, int s, int &L, int &n_blk) {
   const bool skip = (a.skip_bits[s >> 5] >> (s & 31)) & 1u;
-  L = skip ? 0 : a.cu[s + 1] - a.cu[s];
-  n_full = L / BM;
-  tail_cost = (L % BM) ? (L + 63) / 64 : 0;  // 0: no ragged block
+  L = a.cu[s + 1] - a.cu[s];
+  n_blk = skip ? 0 : (L + BM - 1) / BM;
 }
 
-// One thread per tile: tile (s, b) goes to the slot a stable sort by descending cost of the (sequence, block) list
-// would give it -- the number of tiles that cost more, plus the tiles of earlier sequences that cost the same. Both
-// counts have a closed form per sequence, so no sort, no atomics: the table is the same on every call.
+// One thread per tile, in the order the host planner of varlen_attn_fwd uses: sequence by sequence, longest first
+// (equal lengths: lower index first), inside a sequence the last query block first. Tile (s, b) therefore sits behind
+// all blocks of the sequences ordered before s and behind the later blocks of s -- a closed form, so no sort and no
+// atomics, and the table is the same on every call.
 __global__ __launch_bounds__(256) void plan_fwd_tiles_kernel(PlanArgs a, zp_tile *tiles) {
   __shared__ int first_tile[ZP_NOALLOC_MAX_SEQS + 1];
   for (int s = threadIdx.x; s < a.S; s += blockDim.x) {
-    int L, nf, tc;
-    seq_blocks(a, s, L, nf, tc);
-    first_tile[s + 1] = nf + (tc ? 1 : 0);
+    int L, nb;
+    seq_blocks(a, s, L, nb);
+    first_tile[s + 1] = nb;
   }
   __syncthreads();
   if (threadIdx.x == 0) {
@@ -58,26 +57,21 @@ __global__ __launch_bounds__(256) void plan_fwd_tiles_kernel(PlanArgs a, zp_tile
   __syncthreads();
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= a.n_tiles || i >= first_tile[a.S]) return;
-  // the sequence that owns tile i: last s with first_tile[s] <= i
+  // the sequence that owns tile i in (sequence, block) numbering: last s with first_tile[s] <= i
   int lo = 0, hi = a.S - 1;
   while (lo < hi) {
     const int mid = (lo + hi + 1) >> 1;
     if (first_tile[mid] <= i) lo = mid; else hi = mid - 1;
   }
   const int s = lo, b = i - first_tile[s];
-  int L, nf, tc;
-  seq_blocks(a, s, L, nf, tc);
-  const int cost = b < nf ? 2 * (b + 1) : tc;
-  int slot = 0;
+  int L, nb;
+  seq_blocks(a, s, L, nb);
+  int slot = nb - 1 - b;
   for (int s2 = 0; s2 < a.S; s2++) {
-    int L2, nf2, tc2;
-    seq_blocks(a, s2, L2, nf2, tc2);
-    const int gt_full = nf2 - cost / 2;  // full blocks b2 with 2 (b2 + 1) > cost
-    slot += (gt_full > 0 ? gt_full : 0) + (tc2 > cost ? 1 : 0);
-    if (s2 < s) slot += ((cost % 2 == 0 && cost / 2 >= 1 && cost / 2 <= nf2) ? 1 : 0) + (tc2 == cost ? 1 : 0);
+    int L2, nb2;
+    seq_blocks(a, s2, L2, nb2);
+    if (L2 > L || (L2 == L && s2 < s)) slot += nb2;
   }
-  // tiles of the same sequence that cost more: every later block
-  // (already counted above: s2 == s contributes its blocks with a higher cost, none with an equal one)
   zp_tile t;
   t.q_tok0 = a.cu[s] + b * BM;
   t.q_rows = L - b * BM < BM ? L - b * BM : BM;
