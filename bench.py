@@ -206,12 +206,12 @@ class NodeBenchJob:
         j.to_balanced(dq, self.dq_lin); j.to_balanced(dk, self.dk_lin); j.to_balanced(dv, self.dv_lin)
 
 
-DKDV_SHORT_ITERATIONS = 128   # the library's routing rule (head dimension 128): see short_sequence()
+DKDV_SHORT_ITERATIONS = 256   # the library's routing rule (head dimension 128): see short_sequence()
 
 
 def short_sequence(L: int, grp: int, d: int) -> bool:
     """True if the library runs the dK/dV work of a whole sequence of L tokens in its kernel for short sequences (two
-    workgroups per CU): fewer than 128 (64-query tile, head) iterations for the sequence's first key block."""
+    workgroups per CU): fewer than 256 (64-query tile, head) iterations for the sequence's first key block."""
     return d == 128 and ((L + 63) // 64) * grp < DKDV_SHORT_ITERATIONS
 
 
@@ -222,7 +222,13 @@ def kernel_flops(job, label: str) -> float:
     per_gemm_long = 2 * d * Hq * job.pairs_long
     if label in ("attn_bwd_dkdv", "attn_bwd_dkdv_short") and not hasattr(job, "plan"):
         grp = Hq // job.w["Hkv"]
-        short = 2 * d * Hq * pairs_of([L for L in job.lengths if short_sequence(L, grp, d)])
+        # the library's rule: short sequences get the other kernel unless they hold under 30 % of the launch's work
+        # (query tiles visited per key block)
+        work = lambda L: sum((L - j0 + 63) // 64 for j0 in range(0, L, 128))
+        short_seqs = [L for L in job.lengths if short_sequence(L, grp, d)]
+        if 10 * sum(map(work, short_seqs)) < 3 * sum(map(work, job.lengths)):
+            short_seqs = []
+        short = 2 * d * Hq * pairs_of(short_seqs)
         return 4 * (short if label.endswith("_short") else per_gemm_all - short)
     return {"attn_fwd": 2 * (per_gemm_all - per_gemm_long), "attn_fwd_partial": 2 * per_gemm_long,
             "attn_bwd_dq": 3 * per_gemm_all, "attn_bwd_dkdv": 4 * per_gemm_all}.get(label, 0.0)

@@ -199,12 +199,22 @@ int upload_tiles(const std::vector<CostTile> &tiles, void *ws, hipStream_t strea
 // Sequences (or chunk pairs) whose key blocks loop over few (query tile, head) iterations go to the dK/dV kernel that
 // runs two workgroups per CU (head dimension 128 only): a workgroup's fixed cost -- launch, row operands, first tiles,
 // final stores -- is then covered by its neighbour, which is worth more than the other kernel's denser key loop below
-// about 128 iterations of 64 queries. The choice is made per sequence, not per key block, so that the light last blocks
-// of a long sequence stay in the long kernel's launch and fill its tail.
-inline bool kv_rows_are_short(int64_t q_rows_max, int d, int grp) { return d == 128 && ((q_rows_max + 63) / 64) * grp < 128; }
+// about 256 iterations of 64 queries (measured crossover: 8K tokens with one query head per KV head, 2K-4K tokens with
+// 4-8). The choice is made per sequence, not per key block, so that the light last blocks of a long sequence stay in
+// the long kernel's launch and fill its tail.
+inline bool kv_rows_are_short(int64_t q_rows_max, int d, int grp) { return d == 128 && ((q_rows_max + 63) / 64) * grp < 256; }
 // Moves the tiles marked short (aux = 1) behind the others, keeping the order inside both parts; returns the number of
-// long tiles.
+// long tiles. When the short ones hold less than 30 % of the launch's work (query tiles to visit) they stay with the
+// long ones instead: two launches have two tails, and a few light sequences are worth more as the filler of the long
+// kernel's tail than they gain from the other kernel.
 size_t split_kv_tiles(std::vector<CostTile> &kt) {
+  int64_t work = 0, work_short = 0;
+  for (const CostTile &c : kt) {
+    work += c.cost;
+    if (c.t.aux) work_short += c.cost;
+  }
+  if (work_short * 10 < work * 3)
+    for (CostTile &c : kt) c.t.aux = 0;
   return (size_t)(std::stable_partition(kt.begin(), kt.end(), [](const CostTile &c) { return c.t.aux == 0; }) - kt.begin());
 }
 
