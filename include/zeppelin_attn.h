@@ -87,7 +87,8 @@ int varlen_attn_fwd(const void *q, const void *k, const void *v, int64_t q_strid
 
 /* varlen_attn_fwd for callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that
  * forbid hipMalloc. Same arguments and same results (bit for bit) as varlen_attn_fwd without the workspace: the tile
- * table lives in a fixed device array inside the library (ZP_NOALLOC_MAX_TILES records of 32 bytes = 256 KiB, one copy
+ * table lives in a fixed device array inside the library (ZP_NOALLOC_MAX_TILES records of 32 bytes + 1 KiB of work
+ * counters = 257 KiB, one copy
  * per GPU, held until the process ends) and is built on the device from the sequence boundaries, which travel by value
  * in the launch arguments. The call allocates nothing on host or device, reads no host memory from the device and
  * uploads nothing; it enqueues two kernels on `stream`. Limits: S <= ZP_NOALLOC_MAX_SEQS sequences and at most

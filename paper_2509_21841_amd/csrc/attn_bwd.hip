@@ -23,6 +23,7 @@ struct zp_bwd_params {
   __bf16 *dq, *dk, *dv;      // outputs (bf16, overwritten) ...
   int64_t dq_stride, dkv_stride;
   int32_t accumulate;        // ... or, when set, float accumulators of the same shapes that the results are ADDED to
+  zp_work_split work_dq, work_kv, work_kv_short;  // work hand-out of the three launches (counters set by the C ABI, the rest by the launcher)
 };
 
 namespace {
@@ -118,8 +119,10 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) 
   char *Ks = smem;               // [2][64][D]
   char *Vs = smem + 2 * TILEB;   // [2][64][D]
 
+  const int item = zp_item_of_block(p.work_dq, (int *)(smem + 4 * TILEB));
+  if (item < 0) return;
   int unit, hh;
-  zp_block_to_unit(blockIdx.x, p.grp, unit, hh);
+  zp_block_to_unit(item, p.grp, unit, hh);
   if (unit >= p.n_dq_tiles * p.Hkv) return;
   const int tile_idx = unit / p.Hkv, g = unit - tile_idx * p.Hkv;
   const int h = g * p.grp + hh;
@@ -387,8 +390,8 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(D == 64 
   float *Ls = (float *)(smem + 2 * NBUF * TILEB);  // [NBUF][64] -LSE / scale
   float *Ds = Ls + NBUF * 64;                   // [NBUF][64] -D
 
-  const int unit = blockIdx.x;
-  if (unit >= p.n_kv_tiles * p.Hkv) return;
+  const int unit = zp_item_of_block(p.work_kv, (int *)(Ds + NBUF * 64));
+  if (unit < 0 || unit >= p.n_kv_tiles * p.Hkv) return;
   const int tile_idx = unit / p.Hkv, g = unit - tile_idx * p.Hkv;
   const zp_tile t = p.kv_tiles[tile_idx];
 
@@ -644,8 +647,8 @@ __global__ __launch_bounds__(BWD_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) 
   float *Ls = (float *)(Vs + 2 * 64 * D * 2);      // [NBUF][32] -LSE / scale
   float *Ds = Ls + NBUF * QT;                      // [NBUF][32] -D
 
-  const int unit = blockIdx.x;
-  if (unit >= p.n_kv_tiles_short * p.Hkv) return;
+  const int unit = zp_item_of_block(p.work_kv_short, (int *)(Ds + NBUF * QT));
+  if (unit < 0 || unit >= p.n_kv_tiles_short * p.Hkv) return;
   const int tile_idx = unit / p.Hkv, g = unit - tile_idx * p.Hkv;
   const zp_tile t = p.kv_tiles_short[tile_idx];
 
@@ -795,31 +798,37 @@ extern "C" void zp_prof_end(hipStream_t stream);
 
 extern "C" int zp_attn_bwd_block_rows(int d, int which) { (void)d; (void)which; return 128; }
 
-extern "C" int zp_launch_attn_bwd(const zp_bwd_params *p, int d, hipStream_t stream) {
+extern "C" int zp_launch_attn_bwd(const zp_bwd_params *p_in, int d, hipStream_t stream) {
+  zp_bwd_params params = *p_in;
+  zp_bwd_params *p = &params;
   const int dq_units = p->n_dq_tiles * p->Hkv;
   const int kv_units = p->n_kv_tiles * p->Hkv;
+  // item numbering padded to a multiple of 8 (one residue per XCD); the kernels drop the padding
+  int32_t *c = p->work_dq.counters;
+  const int dq_grid = zp_plan_work_split(p->work_dq, c, ((dq_units + 7) / 8) * 8 * p->grp);
+  const int kv_grid = zp_plan_work_split(p->work_kv, c ? c + ZP_COUNTER_BYTES / 4 : nullptr, ((kv_units + 7) / 8) * 8);
+  const int kv_units_short = p->n_kv_tiles_short * p->Hkv;   // only ever non-zero at d = 128
+  const int kv_short_grid = zp_plan_work_split(p->work_kv_short, c ? c + 2 * (ZP_COUNTER_BYTES / 4) : nullptr, ((kv_units_short + 7) / 8) * 8);
   if (dq_units > 0) {
-    const int grid = ((dq_units + 7) / 8) * 8 * p->grp;
     zp_prof_begin("attn_bwd_dq", stream);
-    if (d == 128) hipLaunchKernelGGL((attn_bwd_dq_kernel<128>), dim3(grid), dim3(BWD_NT), 4 * 64 * 128 * 2, stream, *p);
-    else hipLaunchKernelGGL((attn_bwd_dq_kernel<64>), dim3(grid), dim3(BWD_NT), 4 * 64 * 64 * 2, stream, *p);
+    if (d == 128) hipLaunchKernelGGL((attn_bwd_dq_kernel<128>), dim3(dq_grid), dim3(BWD_NT), 4 * 64 * 128 * 2 + 16, stream, *p);
+    else hipLaunchKernelGGL((attn_bwd_dq_kernel<64>), dim3(dq_grid), dim3(BWD_NT), 4 * 64 * 64 * 2 + 16, stream, *p);
     zp_prof_end(stream);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
   }
   if (kv_units > 0) {
     zp_prof_begin("attn_bwd_dkdv", stream);
-    if (d == 128) hipLaunchKernelGGL((attn_bwd_dkdv_kernel<128>), dim3(kv_units), dim3(BWD_NT), 8 * 64 * 128 * 2 + 2048, stream, *p);
-    else hipLaunchKernelGGL((attn_bwd_dkdv_kernel<64>), dim3(kv_units), dim3(BWD_NT), 8 * 64 * 64 * 2 + 2048, stream, *p);
+    if (d == 128) hipLaunchKernelGGL((attn_bwd_dkdv_kernel<128>), dim3(kv_grid), dim3(BWD_NT), 8 * 64 * 128 * 2 + 2048 + 16, stream, *p);
+    else hipLaunchKernelGGL((attn_bwd_dkdv_kernel<64>), dim3(kv_grid), dim3(BWD_NT), 8 * 64 * 64 * 2 + 2048 + 16, stream, *p);
     zp_prof_end(stream);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
   }
-  const int kv_units_short = p->n_kv_tiles_short * p->Hkv;   // only ever non-zero at d = 128
   if (kv_units_short > 0) {
     zp_prof_begin("attn_bwd_dkdv_short", stream);
-    hipLaunchKernelGGL(attn_bwd_dkdv128_kernel, dim3(kv_units_short), dim3(BWD_NT),
-                       2 * ZP_DKDV_NBUF * 32 * 128 * 2 + 2 * 64 * 128 * 2 + 2 * ZP_DKDV_NBUF * 32 * 4, stream, *p);
+    hipLaunchKernelGGL(attn_bwd_dkdv128_kernel, dim3(kv_short_grid), dim3(BWD_NT),
+                       2 * ZP_DKDV_NBUF * 32 * 128 * 2 + 2 * 64 * 128 * 2 + 2 * ZP_DKDV_NBUF * 32 * 4 + 16, stream, *p);
     zp_prof_end(stream);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;

@@ -118,8 +118,10 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   char *Ks = smem;                  // [2][BN][D] bf16
   char *Vs = smem + 2 * C::TILEB;   // [2][BN][D] bf16
 
+  const int item = zp_item_of_block(p.work, (int *)(smem + 4 * C::TILEB));
+  if (item < 0) return;
   int unit, hh;
-  zp_block_to_unit(blockIdx.x, p.grp, unit, hh);
+  zp_block_to_unit(item, p.grp, unit, hh);
   if (unit >= p.n_tiles * p.Hkv) return;
   const int tile_idx = unit / p.Hkv, g = unit - tile_idx * p.Hkv;
   const int h = g * p.grp + hh;
@@ -278,11 +280,13 @@ extern "C" void zp_prof_end(hipStream_t stream);
 extern "C" int zp_launch_attn_fwd(const zp_attn_params *p, int d, int partial, int block_rows, hipStream_t stream) {
   const int units = p->n_tiles * p->Hkv;
   if (units == 0) return 0;
-  const int grid = ((units + 7) / 8) * 8 * p->grp;
+  zp_attn_params q = *p;
+  const int grid = zp_plan_work_split(q.work, p->work.counters, ((units + 7) / 8) * 8 * p->grp);
+  p = &q;
   (void)block_rows;
 #define ZP_FWD_LAUNCH(D, NW, PART)                                                                      \
   do {                                                                                                  \
-    size_t lds = 4 * (size_t)FwdCfg<D, NW>::TILEB;                                                      \
+    size_t lds = 4 * (size_t)FwdCfg<D, NW>::TILEB + 16;                                                    \
     zp_prof_begin(PART ? "attn_fwd_partial" : "attn_fwd", stream);                                      \
     hipLaunchKernelGGL((attn_fwd_kernel<D, NW, PART>), dim3(grid), dim3(NW * 64), lds, stream, *p);     \
     zp_prof_end(stream);                                                                                \

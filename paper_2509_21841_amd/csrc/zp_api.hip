@@ -37,6 +37,7 @@ struct zp_bwd_params {
   __bf16 *dq, *dk, *dv;
   int64_t dq_stride, dkv_stride;
   int32_t accumulate;
+  zp_work_split work_dq, work_kv, work_kv_short;
 };
 int zp_launch_accum_to_bf16(const float *src, void *dst, int64_t n, hipStream_t stream);
 int zp_launch_attn_bwd(const zp_bwd_params *p, int d, hipStream_t stream);
@@ -184,14 +185,31 @@ int64_t count_pair_blocks(const zp_pair *pairs, int n, int bm) {
   return c;
 }
 
+// Every tile table in a workspace is preceded by WS_HEADER bytes of work counters (three sets: a call launches at most
+// three attention kernels), which travel with the table in the same copy and arrive as zeros.
+constexpr size_t WS_HEADER = 3 * ZP_COUNTER_BYTES;
+inline int32_t *ws_counters(void *ws) { return (int32_t *)ws; }
+inline const zp_tile *ws_tiles(void *ws) { return (const zp_tile *)((char *)ws + WS_HEADER); }
+inline size_t tile_table_bytes(size_t n_tiles) { return WS_HEADER + align256(n_tiles * sizeof(zp_tile)); }
+
+// Share of a launch's items that workgroups claim at run time (zp_work_split): half when the items are heavy (32 key
+// or query tiles and more on average, i.e. tens of microseconds each), an eighth when they are light.
+int dyn_div_of(const std::vector<CostTile> &tiles, size_t first, size_t n, int weight) {
+  if (n == 0) return 8;
+  int64_t sum = 0;
+  for (size_t i = first; i < first + n; i++) sum += tiles[i].cost;
+  return sum * weight >= (int64_t)n * 32 ? 2 : 8;
+}
+
 int upload_tiles(const std::vector<CostTile> &tiles, void *ws, hipStream_t stream) {
   if (tiles.empty()) return ZP_OK;
-  const size_t bytes = tiles.size() * sizeof(zp_tile);
+  const size_t bytes = WS_HEADER + tiles.size() * sizeof(zp_tile);
   int slot;
   void *host;
   int rc = pool_acquire(bytes, &slot, &host);
   if (rc) return rc;
-  zp_tile *h = (zp_tile *)host;
+  std::memset(host, 0, WS_HEADER);
+  zp_tile *h = (zp_tile *)((char *)host + WS_HEADER);
   for (size_t i = 0; i < tiles.size(); i++) h[i] = tiles[i].t;
   return pool_upload(slot, host, ws, bytes, stream);
 }
@@ -278,14 +296,14 @@ size_t zp_workspace_bytes(int which_fn, const zp_shape *sh, const int32_t *cu, i
   switch (which_fn) {
     case ZP_FN_FWD: {
       if (check_cu(cu, sh) != ZP_OK) return 0;
-      return align256((size_t)count_blocks(cu, sh->S, zp_attn_fwd_block_rows(sh->d)) * sizeof(zp_tile)) + 256;
+      return tile_table_bytes((size_t)count_blocks(cu, sh->S, zp_attn_fwd_block_rows(sh->d))) + 256;
     }
     case ZP_FN_PARTIAL: {
       if (n_desc < 0) return 0;
       // a pair of q_len rows yields ceil(q_len / block_rows) tiles; bound it with T rows per pair... the exact
       // count needs the pairs, so this bound uses one tile per block_rows tokens of T plus one per pair, per pair
       const int bm = zp_attn_fwd_block_rows(sh->d);
-      return align256((size_t)n_desc * ((size_t)sh->T / bm + 1) * sizeof(zp_tile)) + 256;
+      return tile_table_bytes((size_t)n_desc * ((size_t)sh->T / bm + 1)) + 256;
     }
     case ZP_FN_MERGE: {
       if (n_desc < 0) return 0;
@@ -295,13 +313,13 @@ size_t zp_workspace_bytes(int which_fn, const zp_shape *sh, const int32_t *cu, i
     case ZP_FN_PARTIAL_BWD: {
       if (n_desc < 0) return 0;
       const size_t per_pair = (size_t)sh->T / zp_attn_bwd_block_rows(sh->d, 0) + (size_t)sh->T / zp_attn_bwd_block_rows(sh->d, 1) + 2;
-      return align256((size_t)n_desc * per_pair * sizeof(zp_tile)) + 2 * align256((size_t)sh->Hq * (size_t)sh->T * sizeof(float)) + 512;
+      return tile_table_bytes((size_t)n_desc * per_pair) + 2 * align256((size_t)sh->Hq * (size_t)sh->T * sizeof(float)) + 512;
     }
     case ZP_FN_BWD: {
       if (check_cu(cu, sh) != ZP_OK) return 0;
       const size_t tiles = (size_t)count_blocks(cu, sh->S, zp_attn_bwd_block_rows(sh->d, 0)) +
                            (size_t)count_blocks(cu, sh->S, zp_attn_bwd_block_rows(sh->d, 1));
-      return align256(tiles * sizeof(zp_tile)) + 2 * align256((size_t)sh->Hq * (size_t)sh->T * sizeof(float)) + 512;
+      return tile_table_bytes(tiles) + 2 * align256((size_t)sh->Hq * (size_t)sh->T * sizeof(float)) + 512;
     }
     default: return 0;
   }
@@ -324,12 +342,12 @@ int varlen_attn_fwd(const void *q, const void *k, const void *v, int64_t q_strid
   tiles.reserve((size_t)count_blocks(cu, sh->S, bm));
   plan_whole(cu, sh->S, bm, tiles, seq_skip);
   if (tiles.empty()) return ZP_OK;
-  if ((rc = check_ws(ws, ws_bytes, align256(tiles.size() * sizeof(zp_tile))))) return rc;
+  if ((rc = check_ws(ws, ws_bytes, tile_table_bytes(tiles.size())))) return rc;
   if ((rc = upload_tiles(tiles, ws, (hipStream_t)stream))) return rc;
   zp_attn_params p{};
   p.q = (const __bf16 *)q; p.k = (const __bf16 *)k; p.v = (const __bf16 *)v;
   p.q_stride = q_stride; p.k_stride = k_stride; p.v_stride = v_stride;
-  p.tiles = (const zp_tile *)ws; p.n_tiles = (int32_t)tiles.size();
+  p.tiles = ws_tiles(ws); p.n_tiles = (int32_t)tiles.size(); p.work.counters = ws_counters(ws); p.work.dyn_div = dyn_div_of(tiles, 0, tiles.size(), 1);
   p.Hq = sh->Hq; p.Hkv = sh->Hkv; p.grp = sh->Hq / sh->Hkv;
   p.scale = eff_scale(sh); p.scale_log2 = p.scale * 1.4426950408889634f;
   p.o = o; p.o_stride = o_stride; p.lse = lse; p.lse_stride = sh->T;
@@ -378,12 +396,12 @@ int chunk_attn_partial(const void *q, const void *k, const void *v, int64_t q_st
     }
   }
   sort_by_cost(tiles);
-  if ((rc = check_ws(ws, ws_bytes, align256(tiles.size() * sizeof(zp_tile))))) return rc;
+  if ((rc = check_ws(ws, ws_bytes, tile_table_bytes(tiles.size())))) return rc;
   if ((rc = upload_tiles(tiles, ws, (hipStream_t)stream))) return rc;
   zp_attn_params p{};
   p.q = (const __bf16 *)q; p.k = (const __bf16 *)k; p.v = (const __bf16 *)v;
   p.q_stride = q_stride; p.k_stride = k_stride; p.v_stride = v_stride;
-  p.tiles = (const zp_tile *)ws; p.n_tiles = (int32_t)tiles.size();
+  p.tiles = ws_tiles(ws); p.n_tiles = (int32_t)tiles.size(); p.work.counters = ws_counters(ws); p.work.dyn_div = dyn_div_of(tiles, 0, tiles.size(), 1);
   p.Hq = sh->Hq; p.Hkv = sh->Hkv; p.grp = sh->Hq / sh->Hkv;
   p.scale = eff_scale(sh); p.scale_log2 = p.scale * 1.4426950408889634f;
   p.o = o_part; p.o_stride = (int64_t)sh->Hq * sh->d; p.lse = lse_part; p.lse_stride = part_rows;
@@ -436,12 +454,12 @@ int chunk_attn_update(const void *q, const void *k, const void *v, int64_t q_str
   }
   if (tiles.empty()) return ZP_OK;
   sort_by_cost(tiles);
-  if ((rc = check_ws(ws, ws_bytes, align256(tiles.size() * sizeof(zp_tile))))) return rc;
+  if ((rc = check_ws(ws, ws_bytes, tile_table_bytes(tiles.size())))) return rc;
   if ((rc = upload_tiles(tiles, ws, (hipStream_t)stream))) return rc;
   zp_attn_params p{};
   p.q = (const __bf16 *)q; p.k = (const __bf16 *)k; p.v = (const __bf16 *)v;
   p.q_stride = q_stride; p.k_stride = k_stride; p.v_stride = v_stride;
-  p.tiles = (const zp_tile *)ws; p.n_tiles = (int32_t)tiles.size();
+  p.tiles = ws_tiles(ws); p.n_tiles = (int32_t)tiles.size(); p.work.counters = ws_counters(ws); p.work.dyn_div = dyn_div_of(tiles, 0, tiles.size(), 1);
   p.Hq = sh->Hq; p.Hkv = sh->Hkv; p.grp = sh->Hq / sh->Hkv;
   p.scale = eff_scale(sh); p.scale_log2 = p.scale * 1.4426950408889634f;
   p.o = o_run; p.o_stride = (int64_t)sh->Hq * sh->d; p.lse = lse_run; p.lse_stride = sh->T;
@@ -598,7 +616,7 @@ extern "C" int varlen_attn_bwd(const void *dout, const void *q, const void *k, c
   }
   if (qt.empty() && kt.empty()) return ZP_OK;
   const size_t n_kv_long = split_kv_tiles(kt);
-  const size_t tile_bytes = align256((qt.size() + kt.size()) * sizeof(zp_tile));
+  const size_t tile_bytes = tile_table_bytes(qt.size() + kt.size());
   const size_t dvec_bytes = align256((size_t)sh->Hq * (size_t)sh->T * sizeof(float));
   if ((rc = check_ws(ws, ws_bytes, tile_bytes + 2 * dvec_bytes))) return rc;
   std::vector<CostTile> all(qt);
@@ -611,8 +629,12 @@ extern "C" int varlen_attn_bwd(const void *dout, const void *q, const void *k, c
   p.lse = lse;
   p.dvec = (float *)((char *)ws + tile_bytes);
   p.lse2 = (float *)((char *)ws + tile_bytes + dvec_bytes);
-  p.dq_tiles = (const zp_tile *)ws;
-  p.kv_tiles = (const zp_tile *)ws + qt.size();
+  p.dq_tiles = ws_tiles(ws);
+  p.kv_tiles = ws_tiles(ws) + qt.size();
+  p.work_dq.counters = ws_counters(ws);
+  p.work_dq.dyn_div = dyn_div_of(all, 0, qt.size(), 1);
+  p.work_kv.dyn_div = dyn_div_of(all, qt.size(), n_kv_long, sh->Hq / sh->Hkv);
+  p.work_kv_short.dyn_div = dyn_div_of(all, qt.size() + n_kv_long, kt.size() - n_kv_long, sh->Hq / sh->Hkv);
   p.n_dq_tiles = (int32_t)qt.size(); p.n_kv_tiles = (int32_t)n_kv_long;
   p.kv_tiles_short = p.kv_tiles + n_kv_long; p.n_kv_tiles_short = (int32_t)(kt.size() - n_kv_long);
   p.Hq = sh->Hq; p.Hkv = sh->Hkv; p.grp = sh->Hq / sh->Hkv; p.T = sh->T;
@@ -689,7 +711,7 @@ extern "C" int chunk_attn_partial_bwd(const void *dout, const void *q, const voi
   std::vector<CostTile> qt, kt;
   plan_pairs_bwd(pairs, n_pairs, bmq, bnk, sh->d, sh->Hq / sh->Hkv, qt, kt);
   const size_t n_kv_long = split_kv_tiles(kt);
-  const size_t tile_bytes = align256((qt.size() + kt.size()) * sizeof(zp_tile));
+  const size_t tile_bytes = tile_table_bytes(qt.size() + kt.size());
   const size_t dvec_bytes = align256((size_t)sh->Hq * (size_t)sh->T * sizeof(float));
   if ((rc = check_ws(ws, ws_bytes, tile_bytes + 2 * dvec_bytes))) return rc;
   std::vector<CostTile> all(qt);
@@ -702,8 +724,12 @@ extern "C" int chunk_attn_partial_bwd(const void *dout, const void *q, const voi
   p.lse = lse;
   p.dvec = (float *)((char *)ws + tile_bytes);
   p.lse2 = (float *)((char *)ws + tile_bytes + dvec_bytes);
-  p.dq_tiles = (const zp_tile *)ws;
-  p.kv_tiles = (const zp_tile *)ws + qt.size();
+  p.dq_tiles = ws_tiles(ws);
+  p.kv_tiles = ws_tiles(ws) + qt.size();
+  p.work_dq.counters = ws_counters(ws);
+  p.work_dq.dyn_div = dyn_div_of(all, 0, qt.size(), 1);
+  p.work_kv.dyn_div = dyn_div_of(all, qt.size(), n_kv_long, sh->Hq / sh->Hkv);
+  p.work_kv_short.dyn_div = dyn_div_of(all, qt.size() + n_kv_long, kt.size() - n_kv_long, sh->Hq / sh->Hkv);
   p.n_dq_tiles = (int32_t)qt.size(); p.n_kv_tiles = (int32_t)n_kv_long;
   p.kv_tiles_short = p.kv_tiles + n_kv_long; p.n_kv_tiles_short = (int32_t)(kt.size() - n_kv_long);
   p.Hq = sh->Hq; p.Hkv = sh->Hkv; p.grp = sh->Hq / sh->Hkv; p.T = sh->T;

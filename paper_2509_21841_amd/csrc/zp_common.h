@@ -30,6 +30,54 @@ struct zp_tile {
   int32_t aux;       // kernel specific
 };
 
+// How a launch hands its work items to workgroups. The XCDs of a chip do not run equally fast (on the boxes measured
+// the same four finish an equal share 4-8 % later than the other four), and the hardware deals workgroups to them
+// round-robin, so with one item per workgroup the fast ones idle at the end. Items 0 .. n_static-1 are therefore taken
+// by number (workgroup b runs item b, on XCD b % 8, no cost), and the last ones -- the cheapest of the launch -- are
+// claimed at run time from one counter per XCD by the workgroups behind them, of which the launch holds more than
+// there are items left: a workgroup whose own XCD has none left takes one from a neighbour, surplus workgroups exit.
+// A claim costs its workgroup an atomic round trip (about a microsecond), so launches of light items claim the last
+// eighth and launches of heavy items (dyn_div = 2) the last half.
+// counters: 8 ints, ZP_COUNTER_STRIDE apart, zero before the launch. n_items and n_static are multiples of 8.
+#define ZP_COUNTER_STRIDE 32
+#define ZP_COUNTER_BYTES (8 * ZP_COUNTER_STRIDE * 4)
+struct zp_work_split {
+  int32_t *counters;
+  int32_t n_items, n_static;
+  int32_t dyn_div;  // 1 / dyn_div of the items are claimed at run time (0: the default, 8)
+};
+// Host side: the split and the grid of a launch of n_items (a multiple of 8) items.
+inline int zp_plan_work_split(zp_work_split &ws, int32_t *counters, int n_items) {
+  ws.counters = counters;
+  ws.n_items = n_items;
+  if (n_items < 8 * 128 || counters == nullptr) {  // small launches: every item by number
+    ws.n_static = n_items;
+    return n_items;
+  }
+  const int div = ws.dyn_div >= 2 ? ws.dyn_div : 8;
+  ws.n_static = (n_items / 8 * (div - 1) / div) * 8;
+  const int n_dyn = n_items - ws.n_static;
+  return ws.n_static + ((n_dyn * 3 / 2 + 7) / 8) * 8;
+}
+// Device side: the item of this workgroup, or -1 if there is none left for it. `slot` is one int of LDS. All threads
+// of the workgroup must call it (it holds a barrier for the workgroups that claim).
+__device__ __forceinline__ int zp_item_of_block(const zp_work_split &ws, int *slot) {
+  const int b = blockIdx.x;
+  if (b < ws.n_static) return b;
+  if (threadIdx.x == 0) {
+    const int per = (ws.n_items - ws.n_static) >> 3, x = b & 7;
+    int item = -1;
+    for (int j = 0; j < 8 && item < 0; j++) {
+      const int y = (x + j) & 7;
+      const int k = atomicAdd(ws.counters + y * ZP_COUNTER_STRIDE, 1);
+      if (k < per) item = ws.n_static + 8 * k + y;
+    }
+    *slot = item;
+  }
+  __syncthreads();
+  return __builtin_amdgcn_readfirstlane(*slot);
+}
+
 // Parameters shared by the attention kernels. Strides are token strides in elements.
 struct zp_attn_params {
   const __bf16 *q, *k, *v;
@@ -43,6 +91,7 @@ struct zp_attn_params {
   float *lse;        // [Hq][lse_stride]
   int64_t lse_stride;
   int32_t update;    // partial kernel only: merge the result into the running (o, lse) found at the output rows
+  zp_work_split work;  // which workgroups take their item by number and which claim one (set by the launcher)
 };
 
 // blockIdx -> (unit, head-in-group). Workgroups are dealt to the 8 XCDs round-robin by blockIdx, so

@@ -14,9 +14,9 @@ extern "C" int zp_launch_attn_fwd(const zp_attn_params *p, int d, int partial, i
 extern "C" int zp_attn_fwd_block_rows(int d);
 extern "C" int zp_report_hip_error(int hip_error, const char *what);
 
-// The tile table: ZP_NOALLOC_MAX_TILES records of 32 bytes. One copy per GPU the library runs on, held until the
+// The forward kernel's work counters (ZP_COUNTER_BYTES) and its tile table: ZP_NOALLOC_MAX_TILES records of 32 bytes. One copy per GPU the library runs on, held until the
 // process ends. In host code this name is only a handle for hipGetSymbolAddress, never a device address.
-static __device__ __align__(256) unsigned char scratch[(size_t)ZP_NOALLOC_MAX_TILES * sizeof(zp_tile)];
+static __device__ __align__(256) unsigned char scratch[ZP_COUNTER_BYTES + (size_t)ZP_NOALLOC_MAX_TILES * sizeof(zp_tile)];
 
 namespace {
 
@@ -42,8 +42,10 @@ __device__ __forceinline__ void seq_blocks(const PlanArgs &a, int s, int &L, int
 // (equal lengths: lower index first), inside a sequence the last query block first. Tile (s, b) therefore sits behind
 // all blocks of the sequences ordered before s and behind the later blocks of s -- a closed form, so no sort and no
 // atomics, and the table is the same on every call.
-__global__ __launch_bounds__(256) void plan_fwd_tiles_kernel(PlanArgs a, zp_tile *tiles) {
+__global__ __launch_bounds__(256) void plan_fwd_tiles_kernel(PlanArgs a, int32_t *counters, zp_tile *tiles) {
   __shared__ int first_tile[ZP_NOALLOC_MAX_SEQS + 1];
+  // the attention kernel's work counters start from zero on every call
+  if (blockIdx.x == 0 && threadIdx.x < 8) counters[threadIdx.x * ZP_COUNTER_STRIDE] = 0;
   for (int s = threadIdx.x; s < a.S; s += blockDim.x) {
     int L, nb;
     seq_blocks(a, s, L, nb);
@@ -148,16 +150,16 @@ extern "C" int varlen_attn_fwd_noalloc(const void *q, const void *k, const void 
   int rc = scratch_for_current_device(&tiles);
   if (rc) return rc;
   // Every slot the attention kernel reads is rewritten by the planning kernel of the same call, on the same stream,
-  // so nothing of an earlier call's table survives into this one and nothing needs clearing.
+  // and so are the work counters in front of the table: nothing of an earlier call survives into this one.
   hipLaunchKernelGGL(plan_fwd_tiles_kernel, dim3((unsigned)((n_tiles + 255) / 256)), dim3(256), 0, (hipStream_t)stream, a,
-                     (zp_tile *)tiles);
+                     (int32_t *)tiles, (zp_tile *)((char *)tiles + ZP_COUNTER_BYTES));
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return zp_report_hip_error((int)e, "plan_fwd_tiles launch");
 
   zp_attn_params p{};
   p.q = (const __bf16 *)q; p.k = (const __bf16 *)k; p.v = (const __bf16 *)v;
   p.q_stride = q_stride; p.k_stride = k_stride; p.v_stride = v_stride;
-  p.tiles = (const zp_tile *)tiles; p.n_tiles = (int32_t)n_tiles;
+  p.tiles = (const zp_tile *)((char *)tiles + ZP_COUNTER_BYTES); p.n_tiles = (int32_t)n_tiles; p.work.counters = (int32_t *)tiles;
   p.Hq = sh->Hq; p.Hkv = sh->Hkv; p.grp = sh->Hq / sh->Hkv;
   p.scale = sh->scale > 0.f ? sh->scale : 1.0f / std::sqrt((float)sh->d);
   p.scale_log2 = p.scale * 1.4426950408889634f;
