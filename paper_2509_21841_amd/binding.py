@@ -138,9 +138,10 @@ def _tok_stride(t: torch.Tensor) -> int:
 _ws_cache: dict = {}
 
 
-def workspace(nbytes: int, device, tag: str = "default") -> torch.Tensor:
-    """A cached device scratch tensor of at least nbytes (256-byte aligned by the torch allocator)."""
-    key = (str(device), tag)
+def workspace(nbytes: int, device, tag: str = "default", stream=None) -> torch.Tensor:
+    """A cached device scratch tensor of at least nbytes (256-byte aligned by the torch allocator), one per device,
+    entry point and stream: calls on one stream are ordered and may share it, calls on different streams may not."""
+    key = (str(device), tag, _stream_ptr(stream).value or 0)
     t = _ws_cache.get(key)
     if t is None or t.numel() < nbytes:
         t = torch.empty(max(int(nbytes), 4096), dtype=torch.uint8, device=device)
@@ -170,7 +171,7 @@ def varlen_attn_fwd(q, k, v, cu_seqlens, o=None, lse=None, scale=0.0, ws=None, s
         lse = torch.empty((Hq, T), dtype=torch.float32, device=q.device)
     need = workspace_bytes(FN_FWD, sh, cu)
     if ws is None:
-        ws = workspace(need, q.device, "fwd")
+        ws = workspace(need, q.device, "fwd", stream)
     skip = None if seq_skip is None else np.ascontiguousarray(seq_skip, dtype=np.uint8)
     assert skip is None or len(skip) == len(cu) - 1
     skp = None if skip is None else skip.ctypes.data_as(ctypes.c_void_p)
@@ -211,7 +212,7 @@ def varlen_attn_bwd(dout, q, k, v, o, lse, cu_seqlens, dq=None, dk=None, dv=None
     dv = torch.empty_like(v) if dv is None else dv
     need = workspace_bytes(FN_BWD, sh, cu)
     if ws is None:
-        ws = workspace(need, q.device, "bwd")
+        ws = workspace(need, q.device, "bwd", stream)
     assert _tok_stride(dk) == _tok_stride(dv)
     skip = None if seq_skip is None else np.ascontiguousarray(seq_skip, dtype=np.uint8)
     assert skip is None or len(skip) == len(cu) - 1
@@ -266,7 +267,7 @@ def chunk_attn_partial(q, k, v, pairs, part_rows, o_part=None, lse_part=None, sc
         lse_part = torch.empty((Hq, part_rows), dtype=torch.float32, device=q.device)
     need = workspace_bytes(FN_PARTIAL, sh, None, n)
     if ws is None:
-        ws = workspace(need, q.device, "partial")
+        ws = workspace(need, q.device, "partial", stream)
     _check(lib().chunk_attn_partial(q.data_ptr(), k.data_ptr(), v.data_ptr(), _tok_stride(q), _tok_stride(k), _tok_stride(v),
                                     arr, n, o_part.data_ptr(), lse_part.data_ptr(), int(part_rows), ctypes.byref(sh),
                                     ws.data_ptr(), ws.numel(), _stream_ptr(stream)))
@@ -282,7 +283,7 @@ def chunk_attn_update(q, k, v, pairs, o_run, lse_run, scale=0.0, ws=None, stream
     assert o_run.dtype == torch.float32 and o_run.is_contiguous() and lse_run.dtype == torch.float32 and lse_run.is_contiguous()
     need = workspace_bytes(FN_PARTIAL, sh, None, n)
     if ws is None:
-        ws = workspace(need, q.device, "partial")
+        ws = workspace(need, q.device, "partial", stream)
     _check(lib().chunk_attn_update(q.data_ptr(), k.data_ptr(), v.data_ptr(), _tok_stride(q), _tok_stride(k), _tok_stride(v),
                                    arr, n, o_run.data_ptr(), lse_run.data_ptr(), ctypes.byref(sh), ws.data_ptr(),
                                    ws.numel(), _stream_ptr(stream)))
@@ -300,7 +301,7 @@ def chunk_attn_partial_bwd(dout, q, k, v, o, lse, pairs, dq_acc, dk_acc, dv_acc,
         assert a.dtype == torch.float32 and a.is_contiguous()
     need = workspace_bytes(FN_PARTIAL_BWD, sh, None, n)
     if ws is None:
-        ws = workspace(need, q.device, "partial_bwd")
+        ws = workspace(need, q.device, "partial_bwd", stream)
     _check(lib().chunk_attn_partial_bwd(dout.data_ptr(), q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(),
                                         lse.data_ptr(), _tok_stride(dout), _tok_stride(q), _tok_stride(k), _tok_stride(v),
                                         _tok_stride(o), arr, n, dq_acc.data_ptr(), dk_acc.data_ptr(), dv_acc.data_ptr(),
@@ -405,7 +406,7 @@ def lse_merge(o_part, lse_part, merges, o, lse, ws=None, stream=None):
     arr, n = _merges_array(merges)
     need = workspace_bytes(FN_MERGE, sh, None, n)
     if ws is None:
-        ws = workspace(need, o.device, "merge")
+        ws = workspace(need, o.device, "merge", stream)
     _check(lib().lse_merge(o_part.data_ptr(), lse_part.data_ptr(), int(part_rows), arr, n, o.data_ptr(), _tok_stride(o),
                            lse.data_ptr(), ctypes.byref(sh), ws.data_ptr(), ws.numel(), _stream_ptr(stream)))
     return o, lse

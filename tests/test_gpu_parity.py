@@ -352,6 +352,25 @@ def test_launches_with_a_claimed_tail(lengths, Hq, Hkv, d):
     c.finish()
 
 
+def test_two_streams_keep_their_own_scratch():
+    """Calls issued on two streams overlap on the device; each stream has its own work-list scratch in the binding and
+    the library's staging pool hands every call its own pinned slot, so both must give the single-stream results."""
+    (qa, ka, va, doa), cua = make([900, 1300, 257, 64], 8, 2, 128, 81, with_dout=True)
+    (qb, kb, vb, dob), cub = make([2048, 31, 700], 4, 4, 64, 82, with_dout=True)
+    oa, la = B.varlen_attn_fwd(qa, ka, va, cua); ga = B.varlen_attn_bwd(doa, qa, ka, va, oa, la, cua)
+    ob, lb = B.varlen_attn_fwd(qb, kb, vb, cub); gb = B.varlen_attn_bwd(dob, qb, kb, vb, ob, lb, cub)
+    torch.cuda.synchronize()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    for _ in range(3):
+        with torch.cuda.stream(s1):
+            o1, l1 = B.varlen_attn_fwd(qa, ka, va, cua, stream=s1); g1 = B.varlen_attn_bwd(doa, qa, ka, va, o1, l1, cua, stream=s1)
+        with torch.cuda.stream(s2):
+            o2, l2 = B.varlen_attn_fwd(qb, kb, vb, cub, stream=s2); g2 = B.varlen_attn_bwd(dob, qb, kb, vb, o2, l2, cub, stream=s2)
+        s1.synchronize(); s2.synchronize()
+        for got, ref in ((o1, oa), (l1, la), (o2, ob), (l2, lb), *zip(g1, ga), *zip(g2, gb)):
+            assert torch.equal(got, ref)
+
+
 def test_bwd_closed_forms_on_device():
     """Q = K = 0: the probabilities are uniform over the visible keys, so dQ and dK vanish exactly and
     dV_j = sum over the heads of the group and over queries i >= j of dO_i / (i + 1)."""
