@@ -29,8 +29,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
 HBM_PEAK_GBPS = 8000.0
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script on the default workload,
 # scaled by what the same counters read for a copy of known size (profiles/bench_longtail-128k-gqa32x8_hbm_traffic.txt)
-MEASURED_TRAFFIC_BYTES = {("longtail-128k-gqa32x8", "attn_bwd_dkdv"): (7824202 * 2.00 + 524709 * 1.00) * 1024,
-                          ("longtail-128k-gqa32x8", "attn_bwd_dq"): (3368935 * 2.00 + 1083053 * 1.00) * 1024}
+MEASURED_TRAFFIC_BYTES = {("longtail-128k-gqa32x8", "attn_bwd_dkdv"): (7900334 * 2.00 + 525308 * 1.00) * 1024,
+                          ("longtail-128k-gqa32x8", "attn_bwd_dq"): (3409160 * 2.00 + 1085786 * 1.00) * 1024}
 
 TRAFFIC_SOURCE = "profiles/bench_longtail-128k-gqa32x8_hbm_traffic.txt"
 
