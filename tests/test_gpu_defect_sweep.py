@@ -1,4 +1,5 @@
-"""Defect sweep (NOT a parity claim): many small random configurations through every entry point against the oracle.
+"""Defect sweep (NOT a parity claim): many small random configurations through every entry point, and a few
+medium-size batches through the forward and backward, against the oracle.
 
 Its purpose is breadth: ragged and degenerate lengths, head layouts, chunk counts and scales that the hand-picked
 cases of test_gpu_parity.py do not enumerate. A wrong mask, index or descriptor shows as an error of order one, so the
@@ -69,3 +70,42 @@ def test_random_configurations(seed):
         g = B.remap_tokens(q, idx.to(DEV), 0)
         assert np.array_equal(synth.bf16_bits(g), oracle.remap_tokens(synth.bf16_bits(q), idx.numpy(), 0)), tag
         assert torch.equal(B.remap_tokens(g, idx.to(DEV), 1).view(torch.int16), q.view(torch.int16)), tag
+
+
+@pytest.mark.parametrize("seed", [21, 22])
+def test_random_medium_batches(seed):
+    """Batches of 15-25K tokens with 8-32 query heads: thousands of work items per launch (the run-time claimed tail),
+    both dK/dV kernels and the rule that picks between them, head groupings 1-8. One KV group of each batch against
+    the oracle, with the sweep's defect bound on every element and the stated relative-L2 bound."""
+    rng = np.random.default_rng(seed)
+    for case in range(4):
+        d = int(rng.choice([64, 128, 128])); grp = int(rng.choice([1, 2, 4, 8])); Hkv = int(rng.choice([2, 4, 8]))
+        Hq = Hkv * grp
+        if case == 0:
+            lengths = [int(x) for x in rng.integers(64, 3000, size=int(rng.integers(8, 20)))]
+        elif case == 1:
+            lengths = [int(rng.integers(6000, 12000))] + [int(x) for x in rng.integers(1, 1500, size=int(rng.integers(3, 16)))]
+        elif case == 2:
+            lengths = [int(x) for x in rng.integers(2000, 6000, size=int(rng.integers(3, 6)))]
+        else:
+            lengths = [int(x) for x in rng.choice([127, 128, 129, 1023, 1024, 1025, 2047, 2048, 2049, 4095, 4096, 4097],
+                                                  size=int(rng.integers(4, 10)))]
+        T = sum(lengths)
+        tag = f"seed {seed} case {case}: S={len(lengths)} T={T} max={max(lengths)} Hq={Hq} Hkv={Hkv} d={d}"
+        q, k, v, do = synth.make_qkv(T, Hq, Hkv, d, 1000 * seed + case, DEV, with_dout=True)
+        cu = synth.cu_seqlens(lengths)
+        o, lse = B.varlen_attn_fwd(q, k, v, cu)
+        dq, dk, dv = B.varlen_attn_bwd(do, q, k, v, o, lse, cu)
+        torch.cuda.synchronize()
+        g = int(rng.integers(0, Hkv))
+        heads = list(range(g * grp, (g + 1) * grp))
+        sel = lambda t, hs: widen(t[:, hs].contiguous())
+        ro, rl = oracle.varlen_attn_fwd(sel(q, heads), sel(k, [g]), sel(v, [g]), cu)
+        rdq, rdk, rdv = oracle.varlen_attn_bwd(sel(do, heads), sel(q, heads), sel(k, [g]), sel(v, [g]), cu)
+        kw = dict(maxabs=4e-2, rell2=5e-3)
+        assert_close(tag + " O", sel(o, heads), ro, **kw)
+        assert_lse_close(tag + " LSE", widen(lse[heads].contiguous()), rl)
+        assert_close(tag + " dQ", sel(dq, heads), rdq, **kw)
+        assert_close(tag + " dK", sel(dk, [g]), rdk, **kw)
+        assert_close(tag + " dV", sel(dv, [g]), rdv, **kw)
+        del q, k, v, do, o, lse, dq, dk, dv
