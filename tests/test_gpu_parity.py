@@ -137,6 +137,31 @@ def test_fwd_custom_scale_and_strided_qkv():
     assert_close("O", widen(o), ro); assert_lse_close("LSE", widen(lse), rl)
 
 
+@pytest.mark.parametrize("d", [64, 128])
+def test_bwd_strided_inputs_and_outputs(d):
+    """Q, K, V (and dQ, dK, dV) as slices of one fused [T, Hq + 2 Hkv, d] buffer, dO and O as slices of wider buffers:
+    every token stride differs from heads x d. The results must be bit-identical to those on contiguous tensors."""
+    lengths = [700, 129, 64, 2300]
+    T, Hq, Hkv = sum(lengths), 4, 2
+    cu = synth.cu_seqlens(lengths)
+    fused = synth.normal_bf16((T, Hq + 2 * Hkv, d), 5, 1, DEV)
+    q, k, v = fused[:, :Hq], fused[:, Hq:Hq + Hkv], fused[:, Hq + Hkv:]
+    do_wide = synth.normal_bf16((T, Hq + 3, d), 6, 1, DEV)
+    do = do_wide[:, 2:2 + Hq]
+    qc, kc, vc, doc = q.contiguous(), k.contiguous(), v.contiguous(), do.contiguous()
+    oc, lc = B.varlen_attn_fwd(qc, kc, vc, cu)
+    ref = B.varlen_attn_bwd(doc, qc, kc, vc, oc, lc, cu)
+    o_wide = torch.zeros((T, Hq + 1, d), dtype=torch.bfloat16, device=DEV)
+    o = o_wide[:, 1:]
+    o.copy_(oc)
+    grads = torch.full((T, Hq + 2 * Hkv, d), 7.0, dtype=torch.bfloat16, device=DEV)
+    dq, dk, dv = grads[:, :Hq], grads[:, Hq:Hq + Hkv], grads[:, Hq + Hkv:]
+    B.varlen_attn_bwd(do, q, k, v, o, lc, cu, dq=dq, dk=dk, dv=dv)
+    torch.cuda.synchronize()
+    for got, want in zip((dq, dk, dv), ref):
+        assert torch.equal(got.contiguous().view(torch.int16), want.view(torch.int16))
+
+
 def test_fwd_closed_forms_on_device():
     lengths = [1, 300]
     (q, k, v), cu = make(lengths, 2, 2, 128, 9)
