@@ -49,3 +49,32 @@ def test_noalloc_limits_are_errors():
     with pytest.raises(B.ZpError) as e:
         B.varlen_attn_fwd_noalloc(q, k, v, synth.cu_seqlens(lengths), o, lse)
     assert e.value.code == -5
+
+
+def test_noalloc_forward_replays_from_a_captured_graph():
+    """What the entry point is for: one call recorded into a HIP graph (nothing in it allocates, uploads or clears
+    memory with a memset node), replayed on new contents of the same buffers, each replay against an eager
+    varlen_attn_fwd of the same inputs, with the program's own eager work and synchronisations in between."""
+    dev = "cuda:0"
+    lengths = [900, 129, 0, 1, 2049, 64, 300]
+    Hq, Hkv, d = 8, 2, 128
+    T = int(sum(lengths))
+    cu = np.asarray(synth.cu_seqlens(lengths))
+    q, k, v = synth.make_qkv(T, Hq, Hkv, d, 2201, dev)
+    o = torch.full_like(q, 7.0)
+    lse = torch.full((Hq, T), 7.0, dtype=torch.float32, device=dev)
+    B.varlen_attn_fwd_noalloc(q, k, v, cu, o, lse)      # first call on the device: looks up the array's address
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        B.varlen_attn_fwd_noalloc(q, k, v, cu, o, lse)  # on the capture stream (torch's current stream here)
+    for rep in range(3):
+        q2, k2, v2 = synth.make_qkv(T, Hq, Hkv, d, 2300 + rep, dev)
+        q.copy_(q2); k.copy_(k2); v.copy_(v2)
+        o_ref, lse_ref = B.varlen_attn_fwd(q, k, v, cu)
+        o.fill_(7.0); lse.fill_(7.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(synth.bf16_bits(o), synth.bf16_bits(o_ref)), f"replay {rep}: O differs"
+        assert np.array_equal(lse.cpu().numpy().view(np.uint32), lse_ref.cpu().numpy().view(np.uint32)), f"replay {rep}: LSE differs"
