@@ -40,6 +40,14 @@ def test_noalloc_forward_equals_forward_on_two_calls_in_a_row():
     _run_both([64], 4, 4, 64, 2104)
 
 
+def test_noalloc_at_its_limits():
+    # exactly the largest tile table (8192 blocks of 128 rows, a million tokens), then exactly the most sequences
+    assert B.NOALLOC_MAX_TILES % 16 == 0
+    _run_both([2048] * (B.NOALLOC_MAX_TILES // 16), 1, 1, 64, 2105)
+    rng = np.random.default_rng(2106)
+    _run_both([int(x) for x in rng.integers(0, 300, size=B.NOALLOC_MAX_SEQS)], 2, 1, 64, 2106)
+
+
 def test_noalloc_limits_are_errors():
     dev = "cuda:0"
     lengths = [1] * (B.NOALLOC_MAX_SEQS + 1)
