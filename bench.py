@@ -44,6 +44,8 @@ WORKLOADS = {
     "arxiv-128k-mha32": dict(T=131072, Hq=32, Hkv=32, d=128, seed=1011, mix="table2:arxiv", C=4, bwd=True, remap=True),
     "github-128k-mha32": dict(T=131072, Hq=32, Hkv=32, d=128, seed=1012, mix="table2:github", C=4, bwd=True, remap=True),
     "prolong64k-128k-mha32": dict(T=131072, Hq=32, Hkv=32, d=128, seed=1013, mix="table2:prolong64k", C=4, bwd=True, remap=True),
+    # one sequence that fills the batch (the longest a single GPU sees here): forward as 8 chunks + merge
+    "single-128k-mha8": dict(T=131072, Hq=8, Hkv=8, d=128, seed=1021, mix="single", C=8, bwd=True, remap=False),
     # forward of what ONE device of an 8-device node computes after the hierarchical partitioner has placed the
     # 128K long-tail batch (capacity 20480 tokens per device): its local sequences whole, and for every ring
     # sequence the Q chunks of its ring rank against their causal KV chunks, merged by LSE
@@ -76,6 +78,8 @@ class Job:
             lin_lengths = synth.lengths_table2(T, w["seed"], w["mix"].split(":")[1])
         elif w["mix"] == "longtail":
             lin_lengths, _ = synth.lengths_longtail(T, w["seed"])
+        elif w["mix"] == "single":
+            lin_lengths = [T]
         else:
             lin_lengths = synth.lengths_lognormal(T, w["seed"])
         self.lin_lengths = lin_lengths

@@ -2,7 +2,8 @@
 GQA batch (remap -> forward with the long sequence as 4-chunk pairs + merge -> backward -> inverse remap), the 64K
 lognormal MHA batch, the 256K-token 64/8-head slice (remap -> forward -> inverse remap, remap -> backward -> inverse
 remap; the one shape whose Q holds 2^31 elements, 2^32 bytes) and a batch drawn from the ArXiv length histogram of
-Table 2 (sequences up to 64896 tokens). The oracle checks sampled outputs it can compute one by one: whole short
+Table 2 (sequences up to 64896 tokens), and one 131072-token sequence that fills its batch (forward as 8 chunks + merge,
+the longest key loops and the largest positions any launch here sees). The oracle checks sampled outputs it can compute one by one: whole short
 sequences, the sequence that lies last in the layout (largest offsets), single rows of the longest sequence, dQ rows
 and dK/dV rows at its first keys, in its middle and at its end."""
 import os
@@ -21,7 +22,8 @@ import bench  # noqa: E402
 
 pytestmark = pytest.mark.gpu
 
-WORKLOADS = ["longtail-128k-gqa32x8", "lognormal-64k-mha32", "lognormal-256k-gqa64x8", "arxiv-128k-mha32"]
+WORKLOADS = ["longtail-128k-gqa32x8", "lognormal-64k-mha32", "lognormal-256k-gqa64x8", "arxiv-128k-mha32",
+             "single-128k-mha8"]
 KINDS = ["remap", "O", "LSE", "dQ", "dK", "dV", "properties"]
 # Where the stated max-abs bound of 2e-2 is NOT met (everything else in this file meets it), with the counts and maxima
 # of the seeded inputs (the kernels are deterministic). All of it is dK / dV of the GQA batches: sums over the 4 or 8
@@ -76,7 +78,7 @@ def comparisons(name):
     # element and byte offsets: beyond 2^31 bytes into Q whenever Q is larger than that) on the first and last KV
     # group: forward and backward, all rows
     whole = [s for s in range(len(job.lengths)) if not job.skip[s] and job.lengths[s] <= 12000]
-    last = max(whole, key=lambda s: int(job.cu[s]))
+    last = max(whole, key=lambda s: int(job.cu[s])) if whole else longest   # (a batch of one long sequence has none)
     if job.q.numel() >= 2 ** 31:
         out["properties"].append(("a sampled sequence lies beyond byte offset 2^31 of Q", int(job.cu[last]) * Hq * d * 2 > 2 ** 31))
     for seq in dict.fromkeys((shortest, median, last)):
